@@ -1,0 +1,170 @@
+"""Seeded synthetic inputs for the five workloads.
+
+This module holds no arithmetic of the method itself: it only draws random
+tensors of the stated shapes and distributions and rounds them to the storage
+type.  Both the CPU oracle's tests and the HIP path's tests are fed from here,
+so that they see bit-identical values.
+
+Host generators return float32 numpy arrays whose values are exactly
+representable in the storage type (bf16 workloads are rounded to bf16,
+round-to-nearest-even, once, here).  Device generators (used at full benchmark
+sizes, where drawing 2 GiB on the host would dominate the run) draw with a
+seeded ``torch.Generator`` on the GPU and return torch tensors in the storage
+type; a slice of such a tensor copied to the host feeds the oracle.
+
+Seeds: ``SEED_BASE + config_index`` (config_index 0..4 in the order of the
+workload list below); tensors are drawn in the order Q, K, V / X / X, g, W.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+SEED_BASE = 20260310
+
+# The five workloads (index = config_index).
+WORKLOADS = {
+    0: dict(name="attn_fp32_single_head", kind="attention", dtype="f32",
+            B=1, Hq=1, Hkv=1, Lq=128, Lk=512, d=64, causal=False),
+    1: dict(name="softmax_bf16_32768x4096", kind="softmax", dtype="bf16",
+            rows=32768, n=4096, sigma=2.0),
+    2: dict(name="attn_prefill_bf16_b4h32l2048d128", kind="attention", dtype="bf16",
+            B=4, Hq=32, Hkv=32, Lq=2048, Lk=2048, d=128, causal=False),
+    3: dict(name="attn_decode_gqa_bf16_b16h32kv8l32768d128", kind="decode", dtype="bf16",
+            B=16, Hq=32, Hkv=8, Lq=1, Lk=32768, d=128, num_splits=64),
+    4: dict(name="rmsnorm_gemm_bf16_4096", kind="rmsnorm_gemm", dtype="bf16",
+            M=4096, K=4096, N=4096, eps=1e-6, w_sigma=0.02),
+}
+
+
+# --------------------------------------------------------------------------
+# bf16 storage helpers (host)
+# --------------------------------------------------------------------------
+def bf16_bits(a):
+    """float32 array -> uint16 bf16 bit patterns, round-to-nearest-even."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits):
+    """uint16 bf16 bit patterns -> float32 array (exact)."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_round(a):
+    """float32 array -> float32 array of bf16-representable values (RNE)."""
+    return bf16_bits_to_f32(bf16_bits(a))
+
+
+def _store(a, dtype):
+    a = np.asarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        return bf16_round(a)
+    if dtype == "f32":
+        return a
+    raise ValueError(f"unknown dtype {dtype}")
+
+
+# --------------------------------------------------------------------------
+# host generators
+# --------------------------------------------------------------------------
+def attention_inputs(seed, B, Hq, Hkv, Lq, Lk, d, dtype):
+    """Q[B,Hq,Lq,d], K,V[B,Hkv,Lk,d] i.i.d. N(0,1)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = _store(rng.standard_normal((B, Hq, Lq, d), dtype=np.float32), dtype)
+    k = _store(rng.standard_normal((B, Hkv, Lk, d), dtype=np.float32), dtype)
+    v = _store(rng.standard_normal((B, Hkv, Lk, d), dtype=np.float32), dtype)
+    return q, k, v
+
+
+def softmax_inputs(seed, rows, n, sigma, dtype):
+    """X[rows,n] i.i.d. N(0, sigma^2)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal((rows, n), dtype=np.float32) * np.float32(sigma)
+    return _store(x, dtype)
+
+
+def rmsnorm_gemm_inputs(seed, M, K, N, w_sigma=0.02, dtype="bf16"):
+    """X[M,K] ~ N(0,1), g[K] ~ U[0.5,1.5), W[K,N] ~ N(0, w_sigma^2)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = _store(rng.standard_normal((M, K), dtype=np.float32), dtype)
+    g = _store(rng.random(K, dtype=np.float32) + np.float32(0.5), dtype)
+    w = _store(rng.standard_normal((K, N), dtype=np.float32) * np.float32(w_sigma), dtype)
+    return x, g, w
+
+
+def default_scale(d):
+    return 1.0 / math.sqrt(d)
+
+
+# --------------------------------------------------------------------------
+# torch plumbing: host array <-> tensor in the storage type
+# --------------------------------------------------------------------------
+def to_torch(a, dtype, device="cpu"):
+    """float32 host array of storage-representable values -> torch tensor."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)          # exact: values are representable
+    return t.to(device)
+
+
+def to_numpy(t):
+    """torch tensor (any float dtype, any device) -> float64 host array."""
+    import torch
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+# --------------------------------------------------------------------------
+# device generators (full benchmark sizes)
+# --------------------------------------------------------------------------
+def _torch_dtype(dtype):
+    import torch
+    return {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+
+
+def _randn_device(gen, shape, dtype, device, sigma=1.0, chunk=1 << 27):
+    """Draw N(0, sigma^2) on the device in chunks and store in ``dtype``."""
+    import torch
+    out = torch.empty(shape, dtype=_torch_dtype(dtype), device=device)
+    flat = out.view(-1)
+    n = flat.numel()
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        t = torch.randn(hi - lo, generator=gen, device=device, dtype=torch.float32)
+        if sigma != 1.0:
+            t.mul_(sigma)
+        flat[lo:hi].copy_(t)
+    return out
+
+
+def attention_inputs_device(seed, B, Hq, Hkv, Lq, Lk, d, dtype, device="cuda:0"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    q = _randn_device(gen, (B, Hq, Lq, d), dtype, device)
+    k = _randn_device(gen, (B, Hkv, Lk, d), dtype, device)
+    v = _randn_device(gen, (B, Hkv, Lk, d), dtype, device)
+    return q, k, v
+
+
+def softmax_inputs_device(seed, rows, n, sigma, dtype, device="cuda:0"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    return _randn_device(gen, (rows, n), dtype, device, sigma=sigma)
+
+
+def rmsnorm_gemm_inputs_device(seed, M, K, N, w_sigma=0.02, dtype="bf16", device="cuda:0"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = _randn_device(gen, (M, K), dtype, device)
+    g = (torch.rand(K, generator=gen, device=device, dtype=torch.float32) + 0.5).to(_torch_dtype(dtype))
+    w = _randn_device(gen, (K, N), dtype, device, sigma=w_sigma)
+    return x, g, w

@@ -1,0 +1,374 @@
+"""Pins for the CPU oracle: closed forms, invariants, special cases that reduce
+to a library routine, brute force on tiny inputs, and the paper's own
+equivalence (multi-pass chain == fused == incremental; merge of segment states
+== state of the concatenation).  None of these re-types the oracle's formula:
+a dropped term, wrong sign, wrong index or transposed operand in the oracle
+fails at least one of them.  CPU only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rf_oracle as O
+
+RNG = lambda s: np.random.Generator(np.random.PCG64(s))
+
+
+# ------------------------------------------------------------------ softmax
+def test_softmax_rows_sum_to_one_and_positive():
+    x = RNG(1).standard_normal((37, 513)) * 3.0
+    y = O.safe_softmax(x)
+    assert np.all(y > 0)
+    np.testing.assert_allclose(y.sum(axis=1), 1.0, rtol=0, atol=513 * 1e-15)
+
+
+def test_softmax_shift_invariance():
+    x = RNG(2).standard_normal((5, 64))
+    for c in (-1000.0, 3.25, 700.0):
+        np.testing.assert_allclose(O.safe_softmax(x + c), O.safe_softmax(x), rtol=1e-9, atol=0)
+
+
+def test_softmax_constant_row_is_uniform():
+    for n in (1, 2, 7, 4096):
+        y = O.safe_softmax(np.full((1, n), 12.5))
+        assert np.all(y == 1.0 / n)
+
+
+def test_softmax_two_elements_is_logistic():
+    a, b = 0.7, -1.9
+    y = O.safe_softmax(np.array([[a, b]]))
+    assert y[0, 0] == pytest.approx(1.0 / (1.0 + math.exp(-(a - b))), rel=1e-14)
+    assert y[0, 1] == pytest.approx(1.0 / (1.0 + math.exp(-(b - a))), rel=1e-14)
+
+
+def test_softmax_monotone_and_ratio():
+    x = RNG(3).standard_normal((1, 50))
+    y = O.safe_softmax(x)
+    order_x = np.argsort(x[0])
+    assert np.all(np.diff(y[0][order_x]) >= 0)
+    # y_i / y_j = exp(x_i - x_j): fixes the sign of the exponent
+    assert y[0, 3] / y[0, 9] == pytest.approx(math.exp(x[0, 3] - x[0, 9]), rel=1e-12)
+
+
+def test_softmax_no_overflow_for_large_logits():
+    x = np.array([[800.0, 799.0, -800.0]])
+    y = O.safe_softmax(x)
+    assert np.all(np.isfinite(y))
+    assert y[0, 0] == pytest.approx(1.0 / (1.0 + math.exp(-1.0)), rel=1e-12)
+
+
+def test_softmax_matches_library_float64():
+    x = RNG(4).standard_normal((9, 300)) * 2.0
+    ref = torch.softmax(torch.from_numpy(x), dim=-1).numpy()
+    np.testing.assert_allclose(O.safe_softmax(x), ref, rtol=1e-12, atol=0)
+
+
+def test_softmax_incremental_equals_multipass():
+    for s in range(5):
+        x = RNG(10 + s).standard_normal(1 + 3 * s) * 4.0
+        np.testing.assert_allclose(O.softmax_incremental(x), O.safe_softmax(x[None])[0], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- attention
+def _qkv(seed, B=1, Hq=1, Hkv=1, Lq=3, Lk=5, d=4):
+    r = RNG(seed)
+    return (r.standard_normal((B, Hq, Lq, d)), r.standard_normal((B, Hkv, Lk, d)),
+            r.standard_normal((B, Hkv, Lk, d)))
+
+
+def test_attention_single_key_returns_v0():
+    q, k, v = _qkv(20, Lk=1)
+    o = O.attention(q, k, v, 0.5)
+    for i in range(q.shape[2]):
+        np.testing.assert_allclose(o[0, 0, i], v[0, 0, 0], rtol=1e-15)
+
+
+def test_attention_equal_v_rows():
+    q, k, v = _qkv(21)
+    v[:] = v[:, :, :1, :]
+    o = O.attention(q, k, v, 0.37)
+    np.testing.assert_allclose(o[0, 0], np.broadcast_to(v[0, 0, 0], o[0, 0].shape), rtol=1e-13)
+
+
+def test_attention_zero_keys_gives_column_mean_of_v():
+    q, k, v = _qkv(22, Lk=6)
+    k[:] = 0.0
+    o = O.attention(q, k, v, 1.0)
+    np.testing.assert_allclose(o[0, 0], np.broadcast_to(v[0, 0].mean(axis=0), o[0, 0].shape), rtol=1e-13)
+
+
+def test_attention_dominant_logit_selects_that_v_row():
+    q, k, v = _qkv(23, Lq=1, Lk=6, d=4)
+    q[0, 0, 0] = np.array([1.0, 0.0, 0.0, 0.0])
+    k[0, 0, :, 0] = 0.0
+    k[0, 0, 4, 0] = 200.0
+    o = O.attention(q, k, v, 1.0)
+    np.testing.assert_allclose(o[0, 0, 0], v[0, 0, 4], rtol=1e-12)
+
+
+def test_attention_two_keys_closed_form_fixes_scale_sign_and_operands():
+    # one query, two keys, d=2, all numbers written out by hand
+    q = np.array([[[[1.0, 2.0]]]])
+    k = np.array([[[[0.5, -1.0], [2.0, 0.25]]]])
+    v = np.array([[[[1.0, 10.0], [-2.0, 20.0]]]])
+    scale = 0.5
+    p0 = scale * (1.0 * 0.5 + 2.0 * -1.0)      # -0.75
+    p1 = scale * (1.0 * 2.0 + 2.0 * 0.25)      # 1.25
+    w1 = 1.0 / (1.0 + math.exp(p0 - p1))
+    w0 = 1.0 - w1
+    o = O.attention(q, k, v, scale)
+    np.testing.assert_allclose(o[0, 0, 0], w0 * v[0, 0, 0] + w1 * v[0, 0, 1], rtol=1e-14)
+
+
+def test_attention_per_row_constant_in_logits_is_invisible():
+    # appending a column c to Q and a column of ones to K adds c_i to row i of P
+    q, k, v = _qkv(24, Lq=4, Lk=7, d=3)
+    c = RNG(25).standard_normal((1, 1, 4, 1)) * 50.0
+    q2 = np.concatenate([q, c], axis=3)
+    k2 = np.concatenate([k, np.ones((1, 1, 7, 1))], axis=3)
+    np.testing.assert_allclose(O.attention(q2, k2, v, 0.6), O.attention(q, k, v, 0.6), rtol=1e-9)
+
+
+def test_attention_key_permutation_invariance():
+    q, k, v = _qkv(26, Lq=3, Lk=9)
+    perm = RNG(27).permutation(9)
+    np.testing.assert_allclose(O.attention(q, k[:, :, perm], v[:, :, perm], 0.4),
+                               O.attention(q, k, v, 0.4), rtol=1e-12)
+
+
+def test_attention_causal_row_equals_noncausal_prefix():
+    for (Lq, Lk) in ((5, 5), (3, 7), (1, 4)):
+        q, k, v = _qkv(28, Lq=Lq, Lk=Lk)
+        oc = O.attention(q, k, v, 0.5, causal=True)
+        for i in range(Lq):
+            n = i + (Lk - Lq) + 1
+            on = O.attention(q[:, :, i:i + 1], k[:, :, :n], v[:, :, :n], 0.5)
+            np.testing.assert_allclose(oc[0, 0, i], on[0, 0, 0], rtol=1e-13)
+
+
+def test_attention_gqa_equals_mha_with_repeated_kv():
+    q, k, v = _qkv(29, B=2, Hq=6, Hkv=2, Lq=3, Lk=5, d=4)
+    kr = np.repeat(k, 3, axis=1)
+    vr = np.repeat(v, 3, axis=1)
+    np.testing.assert_allclose(O.attention(q, k, v, 0.5), O.attention(q, kr, vr, 0.5), rtol=1e-14)
+    # and heads must not be mixed up: head 3 reads KV head 1
+    o = O.attention(q, k, v, 0.5)
+    o3 = O.attention(q[:, 3:4], k[:, 1:2], v[:, 1:2], 0.5)
+    np.testing.assert_allclose(o[:, 3:4], o3, rtol=1e-14)
+
+
+def test_attention_matches_library_sdpa_float64():
+    q, k, v = _qkv(30, B=2, Hq=3, Hkv=3, Lq=8, Lk=8, d=16)
+    tq, tk, tv = (torch.from_numpy(a) for a in (q, k, v))
+    for causal in (False, True):
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal, scale=0.3)
+        np.testing.assert_allclose(O.attention(q, k, v, 0.3, causal=causal), ref.numpy(), rtol=1e-11, atol=1e-14)
+
+
+def test_attention_rows_matches_full():
+    q, k, v = _qkv(31, B=2, Hq=4, Hkv=2, Lq=6, Lk=10, d=8)
+    rows = [(0, 0, 0), (1, 3, 5), (0, 2, 3)]
+    for causal in (False, True):
+        full = O.attention(q, k, v, 0.35, causal=causal)
+        part = O.attention_rows(q, k, v, 0.35, causal, rows)
+        for n, (b, h, i) in enumerate(rows):
+            np.testing.assert_allclose(part[n], full[b, h, i], rtol=1e-13)
+
+
+def test_attention_incremental_forms_equal_definition():
+    # the paper's claim: chain of trees == level-1 incremental == tiled incremental
+    for seed, (Lq, Lk, d) in enumerate(((2, 1, 3), (3, 5, 4), (4, 16, 8), (2, 13, 5))):
+        q, k, v = _qkv(40 + seed, Lq=Lq, Lk=Lk, d=d)
+        ref = O.attention(q, k, v, 0.45)[0, 0]
+        for i in range(Lq):
+            np.testing.assert_allclose(O.attention_incremental_row(q[0, 0, i], k[0, 0], v[0, 0], 0.45),
+                                       ref[i], rtol=1e-12)
+        for tile in (1, 2, 3, 5, 128):
+            np.testing.assert_allclose(O.attention_tiled_incremental(q[0, 0], k[0, 0], v[0, 0], 0.45, tile),
+                                       ref, rtol=1e-12)
+    q, k, v = _qkv(50, Lq=6, Lk=9, d=4)
+    refc = O.attention(q, k, v, 0.45, causal=True)[0, 0]
+    for tile in (1, 4, 7):
+        np.testing.assert_allclose(
+            O.attention_tiled_incremental(q[0, 0], k[0, 0], v[0, 0], 0.45, tile, causal=True), refc, rtol=1e-12)
+
+
+# ------------------------------------------------------------ split + merge
+def test_merge_of_two_segments_equals_whole_for_every_split_point():
+    q, k, v = _qkv(60, Lq=1, Lk=8, d=5)
+    whole = O.fused_segment_state(q[0, 0, 0], k[0, 0], v[0, 0], 0.5)
+    ref = O.attention(q, k, v, 0.5)[0, 0, 0]
+    np.testing.assert_allclose(whole[2], ref, rtol=1e-13)
+    for s in range(0, 9):          # includes empty first / last segment
+        a = O.fused_segment_state(q[0, 0, 0], k[0, 0, :s], v[0, 0, :s], 0.5)
+        b = O.fused_segment_state(q[0, 0, 0], k[0, 0, s:], v[0, 0, s:], 0.5)
+        for merged in (O.fused_levelk([a, b]), O.incremental_levelk([a, b])):
+            assert merged[0] == whole[0]
+            assert merged[1] == pytest.approx(whole[1], rel=1e-13)
+            np.testing.assert_allclose(merged[2], whole[2], rtol=1e-12)
+
+
+def test_merge_is_associative_and_commutative():
+    q, k, v = _qkv(61, Lq=1, Lk=9, d=4)
+    segs = [O.fused_segment_state(q[0, 0, 0], k[0, 0, lo:hi], v[0, 0, lo:hi], 0.7)
+            for lo, hi in ((0, 2), (2, 3), (3, 9))]
+    ref = O.attention(q, k, v, 0.7)[0, 0, 0]
+    for order in itertools.permutations(range(3)):
+        s = [segs[i] for i in order]
+        np.testing.assert_allclose(O.fused_levelk(s)[2], ref, rtol=1e-12)
+        np.testing.assert_allclose(O.incremental_levelk(s)[2], ref, rtol=1e-12)
+        left = O.fused_levelk([O.fused_levelk(s[:2]), s[2]])
+        right = O.fused_levelk([s[0], O.fused_levelk(s[1:])])
+        np.testing.assert_allclose(left[2], right[2], rtol=1e-12)
+
+
+def test_identity_state_is_neutral_and_nan_free():
+    q, k, v = _qkv(62, Lq=1, Lk=4, d=3)
+    a = O.fused_segment_state(q[0, 0, 0], k[0, 0], v[0, 0], 0.5)
+    e = (O.NEG_INF, 0.0, np.zeros(3))
+    for states in ([e, a], [a, e], [e, e, a, e]):
+        for f in (O.fused_levelk, O.incremental_levelk):
+            m, t, o = f(states)
+            assert m == a[0] and t == pytest.approx(a[1], rel=1e-15)
+            np.testing.assert_allclose(o, a[2], rtol=1e-14)
+            assert np.all(np.isfinite(o))
+
+
+def test_partial_states_merge_equals_attention_for_any_split_count():
+    q, k, v = _qkv(63, B=2, Hq=4, Hkv=2, Lq=2, Lk=13, d=6)
+    for causal in (False, True):
+        ref = O.attention(q, k, v, 0.4, causal=causal)
+        for S in (1, 2, 3, 5, 13, 64):
+            pm, pt, pacc = O.attention_partial_states(q, k, v, 0.4, causal, S)
+            assert pm.shape == (2, 4, 2, S) and pacc.shape == (2, 4, 2, S, 6)
+            np.testing.assert_allclose(O.merge_states(pm, pt, pacc), ref, rtol=1e-12, atol=1e-15)
+
+
+def test_chunk_weights_sum_to_one():
+    # weight of chunk c is t_c exp(m_c - m) / t; under the literal reading of the
+    # printed combine listing (exponential applied twice) they would not sum to 1
+    q, k, v = _qkv(64, Lq=3, Lk=12, d=4)
+    pm, pt, pacc = O.attention_partial_states(q, k, v, 0.9, False, 4)
+    ones = np.ones_like(pacc[..., :1])
+    # merging "acc = t" (V == 1) must give exactly 1
+    np.testing.assert_allclose(O.merge_states(pm, pt, pt[..., None] * ones), 1.0, rtol=1e-14)
+    m = pm.max(axis=-1, keepdims=True)
+    t = (pt * np.exp(pm - m)).sum(axis=-1, keepdims=True)
+    double = (pt * np.exp(pm - m) * np.exp(pm - m) / t).sum(axis=-1)
+    assert np.all(double < 1.0 - 1e-6)
+
+
+def test_partial_state_of_one_chunk_is_unnormalised():
+    q, k, v = _qkv(65, Lq=1, Lk=3, d=2)
+    pm, pt, pacc = O.attention_partial_states(q, k, v, 1.0, False, 1)
+    p = k[0, 0] @ q[0, 0, 0]
+    assert pm[0, 0, 0, 0] == p.max()
+    assert pt[0, 0, 0, 0] == pytest.approx(sum(math.exp(x - p.max()) for x in p), rel=1e-15)
+    expect = sum(math.exp(p[j] - p.max()) * v[0, 0, j] for j in range(3))
+    np.testing.assert_allclose(pacc[0, 0, 0, 0], expect, rtol=1e-14)
+
+
+def test_split_bounds_cover_range_once():
+    for Lk, S in ((32768, 64), (13, 5), (5, 8), (1, 1), (513, 4)):
+        b = O.split_bounds(Lk, S)
+        assert len(b) == S and b[0][0] == 0 and max(h for _, h in b) == Lk
+        covered = np.zeros(Lk, dtype=int)
+        for lo, hi in b:
+            covered[lo:hi] += 1
+        assert np.all(covered == 1)
+    assert O.split_bounds(32768, 64)[1] == (512, 1024)
+
+
+# --------------------------------------------------------- RMSNorm + linear
+def test_rmsnorm_identity_weight_gives_normalised_rows():
+    x = RNG(70).standard_normal((5, 16))
+    y = O.rmsnorm_gemm(x, np.ones(16), np.eye(16), 0.0)
+    rms = np.sqrt((x ** 2).mean(axis=1, keepdims=True))
+    np.testing.assert_allclose(y, x / rms, rtol=1e-13)
+    np.testing.assert_allclose((y ** 2).mean(axis=1), 1.0, rtol=1e-13)
+
+
+def test_rmsnorm_row_scale_invariance_without_eps():
+    r = RNG(71)
+    x, g, w = r.standard_normal((4, 12)), r.random(12) + 0.5, r.standard_normal((12, 7))
+    y = O.rmsnorm_gemm(x, g, w, 0.0)
+    c = np.array([[0.5], [3.0], [100.0], [1e-3]])
+    np.testing.assert_allclose(O.rmsnorm_gemm(x * c, g, w, 0.0), y, rtol=1e-12)
+
+
+def test_rmsnorm_single_nonzero_entry_closed_form():
+    K, N = 9, 4
+    r = RNG(72)
+    g, w = r.random(K) + 0.5, r.standard_normal((K, N))
+    x = np.zeros((2, K))
+    x[0, 3] = -2.5
+    x[1, 7] = 0.125
+    y = O.rmsnorm_gemm(x, g, w, 0.0)
+    np.testing.assert_allclose(y[0], -math.sqrt(K) * g[3] * w[3], rtol=1e-13)
+    np.testing.assert_allclose(y[1], +math.sqrt(K) * g[7] * w[7], rtol=1e-13)
+
+
+def test_rmsnorm_eps_is_added_to_mean_square():
+    x = np.array([[3.0, 4.0]])                 # mean square 12.5
+    y = O.rmsnorm_gemm(x, np.array([1.0, 1.0]), np.array([[1.0], [0.0]]), 3.5)
+    assert y[0, 0] == pytest.approx(3.0 / math.sqrt(12.5 + 3.5), rel=1e-15)   # 3/4
+
+
+def test_rmsnorm_linear_in_w_and_w_not_transposed():
+    r = RNG(73)
+    x, g = r.standard_normal((3, 6)), r.random(6) + 0.5
+    w1, w2 = r.standard_normal((6, 5)), r.standard_normal((6, 5))
+    y = O.rmsnorm_gemm(x, g, 2.0 * w1 - 3.0 * w2, 1e-6)
+    np.testing.assert_allclose(y, 2.0 * O.rmsnorm_gemm(x, g, w1, 1e-6) - 3.0 * O.rmsnorm_gemm(x, g, w2, 1e-6),
+                               rtol=1e-11, atol=1e-13)
+    assert y.shape == (3, 5)
+
+
+def test_rmsnorm_matches_library_float64():
+    r = RNG(74)
+    x, g, w = r.standard_normal((7, 33)), r.random(33) + 0.5, r.standard_normal((33, 11)) * 0.02
+    tx, tg, tw = (torch.from_numpy(a) for a in (x, g, w))
+    ref = (tx * torch.rsqrt(tx.pow(2).mean(dim=1, keepdim=True) + 1e-6) * tg) @ tw
+    np.testing.assert_allclose(O.rmsnorm_gemm(x, g, w, 1e-6), ref.numpy(), rtol=1e-12, atol=1e-15)
+
+
+def test_rmsnorm_incremental_and_segment_forms_equal_definition():
+    r = RNG(75)
+    x, g, w = r.standard_normal((3, 10)), r.random(10) + 0.5, r.standard_normal((10, 4))
+    ref = O.rmsnorm_gemm(x, g, w, 1e-6)
+    np.testing.assert_allclose(O.rmsnorm_gemm_incremental(x, g, w, 1e-6), ref, rtol=1e-11)
+    for bounds in ([(0, 10)], [(0, 3), (3, 10)], [(0, 1), (1, 2), (2, 9), (9, 10)]):
+        np.testing.assert_allclose(O.rmsnorm_gemm_segments(x, g, w, 1e-6, bounds), ref, rtol=1e-12)
+
+
+# ------------------------------------------------------------ decomposability
+def test_decomposability_identity_and_g_h_factorisation():
+    """F(x,d) (x) F(x0,d0) == F(x,d0) (x) F(x0,d) with (x) = *, and
+    G = F(., d0), H = F(x0, .) / F(x0, d0) reproduce F (Section 4.2)."""
+    r = RNG(80)
+    for _ in range(20):
+        p, p0, m, m0 = r.standard_normal(4) * 3
+        t, t0 = r.random(2) + 0.1
+        vj, v0 = r.standard_normal(2)
+        v0 = v0 if abs(v0) > 0.1 else 1.0
+        lhs = O.F_sumexp(p, m) * O.F_sumexp(p0, m0)
+        rhs = O.F_sumexp(p, m0) * O.F_sumexp(p0, m)
+        assert lhs == pytest.approx(rhs, rel=1e-12)
+        G = O.F_sumexp(p, m0)
+        H = O.F_sumexp(p0, m) / O.F_sumexp(p0, m0)
+        assert G * H == pytest.approx(O.F_sumexp(p, m), rel=1e-12)
+
+        lhs = O.F_weighted(p, vj, m, t) * O.F_weighted(p0, v0, m0, t0)
+        rhs = O.F_weighted(p, vj, m0, t0) * O.F_weighted(p0, v0, m, t)
+        assert lhs == pytest.approx(rhs, rel=1e-12)
+
+        xk, x0, gk, g0, wk, w0 = r.standard_normal(6) + 2.0
+        ss, ss0 = r.random(2) * 10 + 0.1
+        lhs = O.F_rms(xk, gk, wk, ss, 8, 1e-6) * O.F_rms(x0, g0, w0, ss0, 8, 1e-6)
+        rhs = O.F_rms(xk, gk, wk, ss0, 8, 1e-6) * O.F_rms(x0, g0, w0, ss, 8, 1e-6)
+        assert lhs == pytest.approx(rhs, rel=1e-12)
+    # a mapping that is NOT decomposable under (*): (x - d)^2
+    F = lambda x, d: (x - d) ** 2
+    assert F(1.0, 2.0) * F(3.0, 5.0) != pytest.approx(F(1.0, 5.0) * F(3.0, 2.0))

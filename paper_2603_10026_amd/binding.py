@@ -1,0 +1,194 @@
+"""ctypes binding over the C-ABI library ``librf.so``.
+
+Argument marshalling only: every function builds ``rf_tensor`` descriptors
+from torch tensors (PyTorch is used for device memory and streams) and calls
+the entry point of the same name; all arithmetic runs in the HIP kernels.
+There is no fallback: if the library is missing, or an entry point returns an
+error, a Python exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librf.so")
+
+RF_OK = 0
+RF_ERR_INVALID_ARG, RF_ERR_UNSUPPORTED, RF_ERR_ALIGNMENT, RF_ERR_WORKSPACE, RF_ERR_LAUNCH = 1, 2, 3, 4, 5
+RF_F32, RF_BF16 = 0, 1
+RF_MAX_DIMS = 5
+
+ENTRY_POINTS = (
+    "rf_status_string",
+    "rf_describe_cascade",
+    "rf_safe_softmax",
+    "rf_cascade_attention",
+    "rf_cascade_attention_splitk",
+    "rf_merge_states",
+    "rf_rmsnorm_gemm",
+)
+
+
+class RfTensor(ctypes.Structure):
+    _fields_ = [
+        ("data", ctypes.c_void_p),
+        ("dtype", ctypes.c_int),
+        ("ndim", ctypes.c_int32),
+        ("shape", ctypes.c_int64 * RF_MAX_DIMS),
+        ("stride", ctypes.c_int64 * RF_MAX_DIMS),
+    ]
+
+
+class RfStage(ctypes.Structure):
+    _fields_ = [("reduce", ctypes.c_int), ("combine", ctypes.c_int)]
+
+
+class RfError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+_lib = None
+
+
+def load_library():
+    """Load ``librf.so`` (built by ``python -m paper_2603_10026_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_10026_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(RfTensor)
+    lib.rf_status_string.restype = ctypes.c_char_p
+    lib.rf_status_string.argtypes = [ctypes.c_int]
+    lib.rf_describe_cascade.restype = ctypes.c_int
+    lib.rf_describe_cascade.argtypes = [ctypes.c_char_p, ctypes.POINTER(RfStage), ctypes.c_int]
+    lib.rf_safe_softmax.restype = ctypes.c_int
+    lib.rf_safe_softmax.argtypes = [P, P, ctypes.c_int, ctypes.c_void_p]
+    lib.rf_cascade_attention.restype = ctypes.c_int
+    lib.rf_cascade_attention.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_int, ctypes.c_void_p]
+    lib.rf_cascade_attention_splitk.restype = ctypes.c_int
+    lib.rf_cascade_attention_splitk.argtypes = [P, P, P, ctypes.c_int, P, P, P, ctypes.c_float,
+                                                ctypes.c_int, ctypes.c_void_p]
+    lib.rf_merge_states.restype = ctypes.c_int
+    lib.rf_merge_states.argtypes = [P, P, P, P, ctypes.c_void_p]
+    lib.rf_rmsnorm_gemm.restype = ctypes.c_int
+    lib.rf_rmsnorm_gemm.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_void_p]
+    _lib = lib
+    return lib
+
+
+def status_string(code):
+    return load_library().rf_status_string(int(code)).decode()
+
+
+def describe_cascade(entry):
+    """List of (reduce, combine) enum pairs of an entry point's cascade."""
+    lib = load_library()
+    buf = (RfStage * 8)()
+    n = lib.rf_describe_cascade(entry.encode(), buf, 8)
+    if n < 0:
+        raise KeyError(entry)
+    return [(buf[i].reduce, buf[i].combine) for i in range(n)]
+
+
+_DTYPES = {torch.float32: RF_F32, torch.bfloat16: RF_BF16}
+
+
+def tensor_desc(t):
+    """rf_tensor descriptor of a torch tensor (no copy; strides in elements)."""
+    if t.dtype not in _DTYPES:
+        raise TypeError(f"unsupported dtype {t.dtype}")
+    if t.dim() < 1 or t.dim() > RF_MAX_DIMS:
+        raise ValueError("tensor rank must be 1..5")
+    d = RfTensor()
+    d.data = t.data_ptr() if t.numel() > 0 else None
+    d.dtype = _DTYPES[t.dtype]
+    d.ndim = t.dim()
+    for i in range(t.dim()):
+        d.shape[i] = t.shape[i]
+        d.stride[i] = t.stride(i)
+    return d
+
+
+def _stream(stream):
+    """hipStream_t handle: a torch stream, a raw integer handle, or None for
+    torch's current stream."""
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(code, where):
+    if code != RF_OK:
+        raise RfError(code, where)
+
+
+def rf_safe_softmax(x, y=None, axis=-1, stream=None):
+    """y = softmax(x) over the last axis; returns y (allocated if not given)."""
+    lib = load_library()
+    if y is None:
+        y = torch.empty_like(x)
+    dx, dy = tensor_desc(x), tensor_desc(y)
+    _check(lib.rf_safe_softmax(ctypes.byref(dx), ctypes.byref(dy), int(axis), _stream(stream)),
+           "rf_safe_softmax")
+    return y
+
+
+def rf_cascade_attention(q, k, v, scale, causal=False, o=None, stream=None):
+    lib = load_library()
+    if o is None:
+        o = torch.empty_like(q)
+    dq, dk, dv, do = tensor_desc(q), tensor_desc(k), tensor_desc(v), tensor_desc(o)
+    _check(lib.rf_cascade_attention(ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dv),
+                                    ctypes.byref(do), float(scale), int(bool(causal)),
+                                    _stream(stream)), "rf_cascade_attention")
+    return o
+
+
+def alloc_partial_states(q, num_splits):
+    """Caller-owned workspace for the multi-segment path."""
+    B, Hq, Lq, d = q.shape
+    pm = torch.empty((B, Hq, Lq, num_splits), dtype=torch.float32, device=q.device)
+    pl = torch.empty((B, Hq, Lq, num_splits), dtype=torch.float32, device=q.device)
+    pacc = torch.empty((B, Hq, Lq, num_splits, d), dtype=torch.float32, device=q.device)
+    return pm, pl, pacc
+
+
+def rf_cascade_attention_splitk(q, k, v, num_splits, part_m, part_l, part_acc, scale, causal=False,
+                                stream=None):
+    lib = load_library()
+    dq, dk, dv = tensor_desc(q), tensor_desc(k), tensor_desc(v)
+    dm, dl, da = tensor_desc(part_m), tensor_desc(part_l), tensor_desc(part_acc)
+    _check(lib.rf_cascade_attention_splitk(ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dv),
+                                           int(num_splits), ctypes.byref(dm), ctypes.byref(dl),
+                                           ctypes.byref(da), float(scale), int(bool(causal)),
+                                           _stream(stream)), "rf_cascade_attention_splitk")
+    return part_m, part_l, part_acc
+
+
+def rf_merge_states(part_m, part_l, part_acc, o, stream=None):
+    lib = load_library()
+    dm, dl, da, do = tensor_desc(part_m), tensor_desc(part_l), tensor_desc(part_acc), tensor_desc(o)
+    _check(lib.rf_merge_states(ctypes.byref(dm), ctypes.byref(dl), ctypes.byref(da),
+                               ctypes.byref(do), _stream(stream)), "rf_merge_states")
+    return o
+
+
+def rf_rmsnorm_gemm(x, g, w, eps=1e-6, y=None, stream=None):
+    lib = load_library()
+    if y is None:
+        y = torch.empty((x.shape[0], w.shape[1]), dtype=x.dtype, device=x.device)
+    dx, dg, dw, dy = tensor_desc(x), tensor_desc(g), tensor_desc(w), tensor_desc(y)
+    _check(lib.rf_rmsnorm_gemm(ctypes.byref(dx), ctypes.byref(dg), ctypes.byref(dw),
+                               ctypes.byref(dy), float(eps), _stream(stream)), "rf_rmsnorm_gemm")
+    return y

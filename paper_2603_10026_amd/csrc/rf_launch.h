@@ -1,0 +1,50 @@
+// Internal launch interface between the C-ABI layer (argument validation) and
+// the kernel translation units.  Plain pointers and sizes; every function
+// enqueues on `s` and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rf {
+
+// Rows of length n; pitches in elements.  vec_ok: base pointers and pitches
+// allow 128-bit accesses.
+hipError_t launch_softmax(const void* x, void* y, bool is_bf16, int64_t rows, int64_t n,
+                          int64_t x_pitch, int64_t y_pitch, bool vec_ok, hipStream_t s);
+
+// Strides (in elements) of a [B, H, L, d] tensor whose last axis is contiguous.
+struct Strides4 {
+  int64_t b, h, l;
+};
+
+struct AttnShape {
+  int B, Hq, Hkv, Lq, Lk, d;
+  float scale;
+  int causal;
+};
+
+hipError_t launch_attention_f32(const float* q, const float* k, const float* v, float* o,
+                                Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so,
+                                const AttnShape& a, hipStream_t s);
+
+hipError_t launch_attention_bf16(const void* q, const void* k, const void* v, void* o,
+                                 Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so,
+                                 const AttnShape& a, hipStream_t s);
+
+// Partial states are contiguous: part_m, part_l [B,Hq,Lq,S]; part_acc [B,Hq,Lq,S,d].
+hipError_t launch_attention_splitk_bf16(const void* q, const void* k, const void* v,
+                                        Strides4 sq, Strides4 sk, Strides4 sv, int num_splits,
+                                        float* part_m, float* part_l, float* part_acc,
+                                        const AttnShape& a, hipStream_t s);
+
+// Output row (b, h, i) lives at o + b*so.b + h*so.h + i*so.l.
+hipError_t launch_merge_states(const float* part_m, const float* part_l, const float* part_acc,
+                               void* o, bool o_is_bf16, int B, int Hq, int Lq, int S, int d,
+                               Strides4 so, hipStream_t s);
+
+// x [M,K], g [K], w [K,N], y [M,N]; leading dimensions in elements.
+hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w, void* y, int M,
+                                    int K, int N, int64_t ldx, int64_t ldw, int64_t ldy,
+                                    float eps, hipStream_t s);
+
+}  // namespace rf

@@ -1,0 +1,192 @@
+// Safe softmax over the last axis: the max -> sum-exp cascade (paper
+// Section 2.2; Appendix A.2, first two reductions) fused at wavefront level.
+//
+// Kernel 1 (rows that fit in registers): one 64-lane wavefront owns one row.
+// The row is read once with 128-bit loads and stays in registers; the row max
+// and the row sum are reduced lane-locally, then across the wavefront with
+// DPP; the normalised row is written once with 128-bit stores.  HBM traffic is
+// the algorithmic minimum (one read + one write).
+//
+// Kernel 2 (any row length / alignment): one workgroup streams a row, every
+// lane carrying the level-1 incremental state (m, l) (Appendix A.2,
+// incremental form); lane states are merged with the level-k fused expression
+// (Section 3.2 Eq. (11)) across the wavefront and then across wavefronts
+// through LDS; a second sweep over the row writes the result.
+#include "rf_device.h"
+#include "rf_launch.h"
+
+namespace rf {
+
+// ---- element access by storage type --------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+  static constexpr int kPerVec = 8;  // elements per 128-bit access
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(r[i]); f[2 * i + 1] = bf16_hi(r[i]); }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    return r;
+  }
+  static __device__ __forceinline__ float load(const bf16_t* p) { return from_bf16(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = to_bf16(v); }
+};
+template <> struct Elem<float> {
+  static constexpr int kPerVec = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(r[i]);
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
+    return r;
+  }
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+
+constexpr int kSoftmaxWavesPerWg = 4;
+
+// One wavefront per row; NCH 128-bit chunks per lane; n % kPerVec == 0.
+template <typename T, int NCH>
+__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_regs_kernel(
+    const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n, int64_t x_pitch,
+    int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t row = (int64_t)blockIdx.x * kSoftmaxWavesPerWg + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const u32x4* xr = reinterpret_cast<const u32x4*>(x + row * x_pitch);
+  u32x4* yr = reinterpret_cast<u32x4*>(y + row * y_pitch);
+  const int nvec = n / V;
+
+  u32x4 raw[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = c * kWave + lane;
+    if (idx < nvec) raw[c] = __builtin_nontemporal_load(xr + idx);
+  }
+  // cascade stage 1: row max
+  float m = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    if (c * kWave + lane < nvec) {
+      float f[V];
+      Elem<T>::unpack(raw[c], f);
+#pragma unroll
+      for (int i = 0; i < V; ++i) m = fmaxf(m, f[i]);
+    }
+  }
+  m = wave_max(m);
+  // cascade stage 2: sum of exp(x - m), exponentials kept for the epilogue
+  const float mb = -m * kLog2e;
+  float e[NCH][V];
+  float l = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    if (c * kWave + lane < nvec) {
+      float f[V];
+      Elem<T>::unpack(raw[c], f);
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
+        l += e[c][i];
+      }
+    }
+  }
+  l = wave_sum(l);
+  const float inv = 1.0f / l;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = c * kWave + lane;
+    if (idx < nvec) {
+      float f[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) f[i] = e[c][i] * inv;
+      __builtin_nontemporal_store(Elem<T>::pack(f), yr + idx);
+    }
+  }
+}
+
+// One workgroup per row, any n, scalar accesses; two sweeps over the row.
+constexpr int kStreamThreads = 256;
+template <typename T>
+__global__ __launch_bounds__(kStreamThreads) void softmax_row_streaming_kernel(
+    const T* __restrict__ x, T* __restrict__ y, int64_t rows, int64_t n, int64_t x_pitch,
+    int64_t y_pitch) {
+  __shared__ float sm[kStreamThreads / kWave];
+  __shared__ float sl[kStreamThreads / kWave];
+  const int64_t row = blockIdx.x;
+  if (row >= rows) return;
+  const T* xr = x + row * x_pitch;
+  T* yr = y + row * y_pitch;
+  // level-1 incremental state per lane
+  float m = -INFINITY, l = 0.f;
+  for (int64_t j = threadIdx.x; j < n; j += kStreamThreads) {
+    const float v = Elem<T>::load(xr + j);
+    const float mn = fmaxf(m, v);
+    // exp(m - mn) with m = -inf and l = 0 contributes nothing
+    l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((v - mn) * kLog2e);
+    m = mn;
+  }
+  // merge lane states across the wavefront: l_c * exp(m_c - m)
+  const float mw = wave_max(m);
+  float lw = (m == -INFINITY) ? 0.f : l * fast_exp2((m - mw) * kLog2e);
+  lw = wave_sum(lw);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sm[wave] = mw; sl[wave] = lw; }
+  __syncthreads();
+  float mg = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < kStreamThreads / kWave; ++w) mg = fmaxf(mg, sm[w]);
+  float lg = 0.f;
+#pragma unroll
+  for (int w = 0; w < kStreamThreads / kWave; ++w)
+    lg += (sm[w] == -INFINITY) ? 0.f : sl[w] * fast_exp2((sm[w] - mg) * kLog2e);
+  const float inv = 1.0f / lg;
+  const float mb = -mg * kLog2e;
+  for (int64_t j = threadIdx.x; j < n; j += kStreamThreads) {
+    const float v = Elem<T>::load(xr + j);
+    Elem<T>::store(yr + j, fast_exp2(fmaf(v, kLog2e, mb)) * inv);
+  }
+}
+
+template <typename T>
+static hipError_t launch_softmax_t(const T* x, T* y, int64_t rows, int64_t n, int64_t x_pitch,
+                                   int64_t y_pitch, bool vec_ok, hipStream_t s) {
+  constexpr int V = Elem<T>::kPerVec;
+  const int64_t per_chunk = (int64_t)V * kWave;
+  if (vec_ok && n % V == 0 && n <= 16 * per_chunk) {
+    const int nch = (int)((n + per_chunk - 1) / per_chunk);
+    const unsigned grid = (unsigned)((rows + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg);
+    const dim3 block(kSoftmaxWavesPerWg * kWave);
+#define RF_SOFTMAX_CASE(N)                                                              \
+  hipLaunchKernelGGL((softmax_row_in_regs_kernel<T, N>), dim3(grid), block, 0, s, x, y, \
+                     rows, (int)n, x_pitch, y_pitch)
+    if (nch <= 1) RF_SOFTMAX_CASE(1);
+    else if (nch <= 2) RF_SOFTMAX_CASE(2);
+    else if (nch <= 4) RF_SOFTMAX_CASE(4);
+    else if (nch <= 8) RF_SOFTMAX_CASE(8);
+    else RF_SOFTMAX_CASE(16);
+#undef RF_SOFTMAX_CASE
+  } else {
+    hipLaunchKernelGGL((softmax_row_streaming_kernel<T>), dim3((unsigned)rows),
+                       dim3(kStreamThreads), 0, s, x, y, rows, n, x_pitch, y_pitch);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax(const void* x, void* y, bool is_bf16, int64_t rows, int64_t n,
+                          int64_t x_pitch, int64_t y_pitch, bool vec_ok, hipStream_t s) {
+  if (is_bf16)
+    return launch_softmax_t<bf16_t>((const bf16_t*)x, (bf16_t*)y, rows, n, x_pitch, y_pitch,
+                                    vec_ok, s);
+  return launch_softmax_t<float>((const float*)x, (float*)y, rows, n, x_pitch, y_pitch, vec_ok, s);
+}
+
+}  // namespace rf

@@ -1,0 +1,142 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, describes its cascades, and rejects bad
+arguments with the documented status codes before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2603_10026_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2603_10026_amd import build
+        build.build_library(verbose=False)
+    return B.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rf.h")).read()
+    return sorted(set(re.findall(r"RF_API\s+[\w\s\*]+?\b(rf_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert _declared_symbols() == sorted(B.ENTRY_POINTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert B.status_string(0) == "RF_OK"
+    assert B.status_string(B.RF_ERR_ALIGNMENT) == "RF_ERR_ALIGNMENT"
+    assert B.status_string(99) == "RF_ERR_UNKNOWN"
+
+
+def test_describe_cascade(lib):
+    MAX, SUM, ADD, MUL = 0, 2, 0, 1
+    assert B.describe_cascade("rf_safe_softmax") == [(MAX, ADD), (SUM, MUL)]
+    assert B.describe_cascade("rf_cascade_attention") == [(MAX, ADD), (SUM, MUL), (SUM, MUL)]
+    assert B.describe_cascade("rf_rmsnorm_gemm") == [(SUM, MUL), (SUM, MUL)]
+    with pytest.raises(KeyError):
+        B.describe_cascade("nope")
+
+
+def _desc(shape, dtype=B.RF_BF16, data=0x1000, stride=None):
+    d = B.RfTensor()
+    d.data = data
+    d.dtype = dtype
+    d.ndim = len(shape)
+    st = 1
+    strides = [0] * len(shape)
+    for i in range(len(shape) - 1, -1, -1):
+        strides[i] = st
+        st *= shape[i]
+    if stride is not None:
+        strides = list(stride)
+    for i, s in enumerate(shape):
+        d.shape[i] = s
+        d.stride[i] = strides[i]
+    return d
+
+
+def _r(x):
+    return ctypes.byref(x)
+
+
+def test_softmax_validation(lib):
+    x, y = _desc([4, 64]), _desc([4, 64])
+    assert lib.rf_safe_softmax(None, _r(y), -1, None) == B.RF_ERR_INVALID_ARG
+    assert lib.rf_safe_softmax(_r(x), _r(_desc([4, 32])), -1, None) == B.RF_ERR_INVALID_ARG
+    assert lib.rf_safe_softmax(_r(x), _r(_desc([4, 64], dtype=B.RF_F32)), -1, None) == B.RF_ERR_UNSUPPORTED
+    assert lib.rf_safe_softmax(_r(x), _r(y), 0, None) == B.RF_ERR_UNSUPPORTED      # not the last axis
+    assert lib.rf_safe_softmax(_r(x), _r(y), 2, None) == B.RF_ERR_INVALID_ARG
+    assert lib.rf_safe_softmax(_r(_desc([4, 64], data=None)), _r(y), -1, None) == B.RF_ERR_INVALID_ARG
+    assert lib.rf_safe_softmax(_r(_desc([4, 64], stride=[128, 2])), _r(y), -1, None) == B.RF_ERR_UNSUPPORTED
+    # zero-sized problem: OK, nothing launched
+    assert lib.rf_safe_softmax(_r(_desc([0, 64], data=None)), _r(_desc([0, 64], data=None)), -1, None) == B.RF_OK
+
+
+def test_attention_validation(lib):
+    q, k, v, o = _desc([2, 8, 16, 128]), _desc([2, 2, 32, 128]), _desc([2, 2, 32, 128]), _desc([2, 8, 16, 128])
+    f = lib.rf_cascade_attention
+    assert f(None, _r(k), _r(v), _r(o), 1.0, 0, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(q), _r(_desc([2, 3, 32, 128])), _r(_desc([2, 3, 32, 128])), _r(o), 1.0, 0, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(q), _r(k), _r(_desc([2, 2, 31, 128])), _r(o), 1.0, 0, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(q), _r(_desc([2, 2, 32, 128], dtype=B.RF_F32)), _r(v), _r(o), 1.0, 0, None) == B.RF_ERR_UNSUPPORTED
+    q96 = _desc([2, 8, 16, 96])
+    kv96 = _desc([2, 2, 32, 96])
+    assert f(_r(q96), _r(kv96), _r(kv96), _r(_desc([2, 8, 16, 96])), 1.0, 0, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([2, 8, 16, 128], data=0x1008)), _r(k), _r(v), _r(o), 1.0, 0, None) == B.RF_ERR_ALIGNMENT
+    assert f(_r(q), _r(k), _r(v), _r(_desc([2, 8, 16, 64])), 1.0, 0, None) == B.RF_ERR_INVALID_ARG
+
+
+def test_splitk_and_merge_validation(lib):
+    q, k, v = _desc([2, 8, 1, 128]), _desc([2, 2, 64, 128]), _desc([2, 2, 64, 128])
+    F32 = B.RF_F32
+    pm, pl, pa = _desc([2, 8, 1, 4], F32), _desc([2, 8, 1, 4], F32), _desc([2, 8, 1, 4, 128], F32)
+    f = lib.rf_cascade_attention_splitk
+    assert f(_r(q), _r(k), _r(v), 0, _r(pm), _r(pl), _r(pa), 1.0, 0, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(q), _r(k), _r(v), 5, _r(pm), _r(pl), _r(pa), 1.0, 0, None) == B.RF_ERR_WORKSPACE
+    assert f(_r(q), _r(k), _r(v), 4, _r(_desc([2, 8, 1, 4])), _r(pl), _r(pa), 1.0, 0, None) == B.RF_ERR_WORKSPACE
+    qf = _desc([2, 8, 1, 128], F32)
+    kf = _desc([2, 2, 64, 128], F32)
+    assert f(_r(qf), _r(kf), _r(kf), 4, _r(pm), _r(pl), _r(pa), 1.0, 0, None) == B.RF_ERR_UNSUPPORTED
+    q64, k64 = _desc([2, 8, 1, 64]), _desc([2, 2, 64, 64])
+    pa64 = _desc([2, 8, 1, 4, 64], F32)
+    assert f(_r(q64), _r(k64), _r(k64), 4, _r(pm), _r(pl), _r(pa64), 1.0, 0, None) == B.RF_ERR_UNSUPPORTED
+    o = _desc([2, 8, 1, 128])
+    g = lib.rf_merge_states
+    assert g(_r(pm), _r(pl), _r(pa), None, None) == B.RF_ERR_INVALID_ARG
+    assert g(_r(pm), _r(_desc([2, 8, 1, 5], F32)), _r(pa), _r(o), None) == B.RF_ERR_WORKSPACE
+    assert g(_r(pm), _r(pl), _r(pa), _r(_desc([2, 8, 1, 64])), None) == B.RF_ERR_INVALID_ARG
+    assert g(_r(pm), _r(pl), _r(_desc([2, 8, 1, 4, 128], F32, data=0x1004)), _r(o), None) == B.RF_ERR_ALIGNMENT
+
+
+def test_rmsnorm_gemm_validation(lib):
+    x, g, w, y = _desc([16, 128]), _desc([128]), _desc([128, 64]), _desc([16, 64])
+    f = lib.rf_rmsnorm_gemm
+    assert f(_r(x), _r(g), _r(w), None, 1e-6, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(_desc([64])), _r(w), _r(y), 1e-6, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(g), _r(_desc([128, 64], dtype=B.RF_F32)), _r(y), 1e-6, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([16, 96])), _r(_desc([96])), _r(_desc([96, 64])), _r(y), 1e-6, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(x), _r(g), _r(_desc([128, 60])), _r(_desc([16, 60])), 1e-6, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(x), _r(g), _r(_desc([128, 64], data=0x1002)), _r(y), 1e-6, None) == B.RF_ERR_ALIGNMENT
+    assert f(_r(_desc([0, 128], data=None)), _r(g), _r(w), _r(_desc([0, 64], data=None)), 1e-6, None) == B.RF_OK
+
+
+def test_binding_descriptor_from_torch_tensor():
+    t = torch.zeros((3, 4, 8), dtype=torch.bfloat16)[:, 1:3]
+    d = B.tensor_desc(t)
+    assert d.ndim == 3 and list(d.shape[:3]) == [3, 2, 8] and list(d.stride[:3]) == [32, 8, 1]
+    assert d.dtype == B.RF_BF16 and d.data == t.data_ptr()
+    with pytest.raises(TypeError):
+        B.tensor_desc(torch.zeros(4, dtype=torch.float16))

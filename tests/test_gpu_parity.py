@@ -1,0 +1,266 @@
+"""GPU parity: every entry point of the C-ABI library against the fp64 CPU
+oracle, element by element, on seeded inputs that span several tiles and a
+ragged tail, plus the degenerate cases.
+
+Tolerances (fixed by the benchmark spec): max|err| <= 1e-5 * max|ref| for
+fp32 inputs, <= 2e-2 * max|ref| for bf16 inputs, max|ref| taken over the whole
+output tensor.  A relative-RMS bound (much tighter than the max-norm rule) is
+asserted as well so that a systematic error cannot hide behind one large
+reference value.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rf_oracle as O
+from paper_2603_10026_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+RMS_TOL = {"f32": 2e-6, "bf16": 6e-3}
+
+
+@pytest.fixture(scope="module")
+def rf():
+    from paper_2603_10026_amd import binding
+    binding.load_library()          # raises if the HIP library is missing
+    return binding
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def check(out, ref, dtype, what):
+    out = I.to_numpy(out)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert out.shape == ref.shape, (what, out.shape, ref.shape)
+    assert np.all(np.isfinite(out)), f"{what}: non-finite output"
+    scale = float(np.max(np.abs(ref))) if ref.size else 0.0
+    err = float(np.max(np.abs(out - ref))) if ref.size else 0.0
+    rms = float(np.sqrt(np.mean((out - ref) ** 2)) / max(np.sqrt(np.mean(ref ** 2)), 1e-300)) if ref.size else 0.0
+    print(f"        {what}: max|err|={err:.3e} max|ref|={scale:.3e} ratio={err / max(scale, 1e-300):.2e} relrms={rms:.2e}",
+          flush=True)
+    assert err <= TOL[dtype] * scale, f"{what}: max|err| {err:.3e} > {TOL[dtype]} * {scale:.3e}"
+    assert rms <= RMS_TOL[dtype], f"{what}: rel rms {rms:.3e}"
+
+
+# ------------------------------------------------------------------ softmax
+@pytest.mark.parametrize("dtype,rows,n", [
+    ("bf16", 4, 4096), ("bf16", 37, 512), ("bf16", 5, 8), ("bf16", 3, 1000), ("bf16", 130, 2048),
+    ("bf16", 7, 1003), ("bf16", 2, 9000), ("bf16", 1, 1), ("bf16", 3, 8192),
+    ("f32", 9, 4096), ("f32", 3, 300), ("f32", 2, 5000), ("f32", 6, 1024), ("f32", 5, 7),
+])
+def test_softmax_shapes(rf, dtype, rows, n):
+    say(f"softmax {dtype} rows={rows} n={n}")
+    x = I.softmax_inputs(I.SEED_BASE + 1, rows, n, 2.0, dtype)
+    y = rf.rf_safe_softmax(I.to_torch(x, dtype, DEV))
+    torch.cuda.synchronize()
+    check(y, O.safe_softmax(x), dtype, "softmax")
+
+
+def test_softmax_special_rows_and_inplace(rf):
+    say("softmax special rows, in place")
+    n = 4096
+    x = I.softmax_inputs(11, 6, n, 2.0, "bf16")
+    x[0, :] = 1.5                      # all equal -> 1/n
+    x[1, :] = -3.0
+    x[1, 17] = 80.0                    # one dominant logit
+    x[2, :] = -80.0
+    x[2, 5] = -79.0                    # very negative logits
+    x[3, :] = 0.0
+    x[3, -1] = 30.0                    # dominant logit in the last lane's tail
+    t = I.to_torch(x, "bf16", DEV)
+    ref = O.safe_softmax(x)
+    y = rf.rf_safe_softmax(t, t)       # in place
+    torch.cuda.synchronize()
+    assert y.data_ptr() == t.data_ptr()
+    check(t, ref, "bf16", "softmax in place")
+    out = I.to_numpy(t)
+    assert np.all(out[0] == out[0, 0]) and abs(out[0, 0] * n - 1.0) <= 1e-2
+    assert out[1, 17] == 1.0
+
+
+def test_softmax_strided_rows_and_3d(rf):
+    say("softmax pitched 2-D view and contiguous 3-D")
+    big = I.softmax_inputs(12, 16, 1024, 2.0, "bf16")
+    tb = I.to_torch(big, "bf16", DEV)
+    xv = tb[:, :512]                   # row pitch 1024, row length 512
+    y = torch.zeros_like(tb)
+    rf.rf_safe_softmax(xv, y[:, 512:])
+    torch.cuda.synchronize()
+    check(y[:, 512:], O.safe_softmax(big[:, :512]), "bf16", "softmax pitched")
+    assert float(y[:, :512].abs().max()) == 0.0
+    x3 = big.reshape(4, 4, 1024)
+    y3 = rf.rf_safe_softmax(I.to_torch(x3, "bf16", DEV))
+    torch.cuda.synchronize()
+    check(y3, O.safe_softmax(x3), "bf16", "softmax 3-D")
+    # odd pitch: rows not 16-byte aligned -> scalar streaming path
+    xo = tb[:, 1:1 + 333]
+    yo = rf.rf_safe_softmax(xo, torch.empty((16, 333), dtype=torch.bfloat16, device=DEV))
+    torch.cuda.synchronize()
+    check(yo, O.safe_softmax(big[:, 1:334]), "bf16", "softmax unaligned")
+
+
+def test_softmax_empty(rf):
+    say("softmax empty")
+    x = torch.empty((0, 128), dtype=torch.bfloat16, device=DEV)
+    assert rf.rf_safe_softmax(x).shape == (0, 128)
+
+
+# ---------------------------------------------------------------- attention
+ATTN_CASES = [
+    # dtype, B, Hq, Hkv, Lq, Lk, d, causal
+    ("f32", 1, 1, 1, 128, 512, 64, False),      # workload 0
+    ("f32", 1, 2, 2, 1, 1, 64, False),
+    ("f32", 2, 2, 1, 17, 33, 64, False),
+    ("f32", 1, 3, 3, 17, 17, 64, True),
+    ("f32", 1, 2, 2, 5, 40, 64, True),
+    ("f32", 1, 1, 1, 40, 513, 128, False),
+    ("f32", 1, 4, 2, 33, 33, 128, True),
+    ("f32", 1, 1, 1, 20, 7, 64, True),          # Lk < Lq: first rows see no key
+    ("bf16", 1, 2, 2, 256, 256, 128, False),
+    ("bf16", 1, 2, 2, 256, 256, 128, True),
+    ("bf16", 2, 4, 2, 130, 193, 128, False),
+    ("bf16", 1, 2, 1, 129, 129, 128, True),
+    ("bf16", 1, 1, 1, 127, 63, 128, True),      # Lk < Lq
+    ("bf16", 1, 2, 2, 1, 300, 128, False),
+    ("bf16", 1, 1, 1, 64, 1, 128, False),
+    ("bf16", 1, 2, 2, 200, 200, 64, False),
+    ("bf16", 1, 2, 1, 200, 260, 64, True),
+    ("bf16", 1, 1, 1, 384, 1024, 128, True),
+]
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,Lq,Lk,d,causal", ATTN_CASES)
+def test_attention_shapes(rf, dtype, B, Hq, Hkv, Lq, Lk, d, causal):
+    say(f"attention {dtype} B{B} Hq{Hq} Hkv{Hkv} Lq{Lq} Lk{Lk} d{d} causal={causal}")
+    q, k, v = I.attention_inputs(I.SEED_BASE, B, Hq, Hkv, Lq, Lk, d, dtype)
+    scale = I.default_scale(d)
+    o = rf.rf_cascade_attention(I.to_torch(q, dtype, DEV), I.to_torch(k, dtype, DEV),
+                                I.to_torch(v, dtype, DEV), scale, causal)
+    torch.cuda.synchronize()
+    check(o, O.attention(q, k, v, scale, causal), dtype, "attention")
+
+
+def test_attention_extreme_logits_and_strided_heads(rf):
+    say("attention bf16: large logits, [B,L,H,d] memory order")
+    B, H, L, d = 1, 2, 160, 128
+    q, k, v = I.attention_inputs(77, B, H, H, L, L, d, "bf16")
+    q[0, 0, 3] *= 30.0                 # logits of +-100 and more: tests the max subtraction
+    k[0, 1, 100] = I.bf16_round(q[0, 1, 50] * 4.0)
+    scale = I.default_scale(d)
+    # store as [B, L, H, d] and pass permuted views (head stride = d)
+    tq, tk, tv = (I.to_torch(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), "bf16", DEV).permute(0, 2, 1, 3)
+                  for a in (q, k, v))
+    o = torch.empty((B, L, H, d), dtype=torch.bfloat16, device=DEV).permute(0, 2, 1, 3)
+    rf.rf_cascade_attention(tq, tk, tv, scale, False, o=o)
+    torch.cuda.synchronize()
+    check(o, O.attention(q, k, v, scale, False), "bf16", "attention strided")
+
+
+def test_attention_empty_keys(rf):
+    say("attention Lk=0 -> zeros")
+    q = torch.ones((1, 1, 5, 64), dtype=torch.float32, device=DEV)
+    kv = torch.empty((1, 1, 0, 64), dtype=torch.float32, device=DEV)
+    o = rf.rf_cascade_attention(q, kv, kv, 1.0)
+    torch.cuda.synchronize()
+    assert float(o.abs().max()) == 0.0
+
+
+# ------------------------------------------------------------ split + merge
+SPLIT_CASES = [
+    # B, Hq, Hkv, Lq, Lk, S, causal
+    (2, 8, 2, 1, 1000, 4, False),      # chunk 250: not a multiple of the 32-key step
+    (1, 4, 1, 1, 100, 64, False),      # chunk 2: most chunks tiny, many empty
+    (1, 32, 8, 1, 2048, 4, False),     # workload-3 head layout, chunk 512
+    (1, 32, 1, 1, 700, 3, False),      # 32 rows share one KV head: two row tiles
+    (1, 4, 2, 3, 300, 5, True),        # Lq > 1, causal, fully masked chunks for early rows
+    (1, 2, 2, 1, 1, 1, False),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Lq,Lk,S,causal", SPLIT_CASES)
+def test_splitk_partial_states_and_merge(rf, B, Hq, Hkv, Lq, Lk, S, causal):
+    say(f"splitk B{B} Hq{Hq} Hkv{Hkv} Lq{Lq} Lk{Lk} S{S} causal={causal}")
+    d = 128
+    q, k, v = I.attention_inputs(I.SEED_BASE + 3, B, Hq, Hkv, Lq, Lk, d, "bf16")
+    scale = I.default_scale(d)
+    tq, tk, tv = (I.to_torch(a, "bf16", DEV) for a in (q, k, v))
+    pm, pl, pacc = rf.alloc_partial_states(tq, S)
+    pm.fill_(float("nan")); pl.fill_(float("nan")); pacc.fill_(float("nan"))
+    rf.rf_cascade_attention_splitk(tq, tk, tv, S, pm, pl, pacc, scale, causal)
+    o = torch.empty_like(tq)
+    rf.rf_merge_states(pm, pl, pacc, o)
+    torch.cuda.synchronize()
+    rm, rl, racc = O.attention_partial_states(q, k, v, scale, causal, S)
+    gm, gl, gacc = I.to_numpy(pm), I.to_numpy(pl), I.to_numpy(pacc)
+    # identity chunks are exactly (-inf, 0, 0)
+    ident = ~np.isfinite(rm)
+    assert np.array_equal(ident, ~np.isfinite(gm))
+    assert np.all(gm[ident] == -np.inf) and np.all(gl[ident] == 0.0) and np.all(gacc[ident] == 0.0)
+    # the state is unique up to the reference point m: compare m, and (l, acc) moved to the oracle's m
+    fin = ~ident
+    np.testing.assert_allclose(gm[fin], rm[fin], rtol=0, atol=2e-2 * max(1.0, float(np.max(np.abs(rm[fin])))))
+    shift = np.where(fin, np.exp(np.where(fin, gm - rm, 0.0)), 0.0)
+    check(torch.from_numpy(gl * shift), rl, "bf16", "partial l")
+    check(torch.from_numpy(gacc * shift[..., None]), racc, "bf16", "partial acc")
+    check(o, O.attention(q, k, v, scale, causal), "bf16", "merged == attention over the whole key axis")
+
+
+@pytest.mark.parametrize("S,d,out_dtype", [(1, 128, "bf16"), (3, 128, "bf16"), (64, 128, "bf16"),
+                                           (300, 128, "f32"), (5, 64, "f32"), (7, 4, "f32"), (2, 256, "bf16")])
+def test_merge_states_alone(rf, S, d, out_dtype):
+    say(f"merge S{S} d{d} -> {out_dtype}")
+    rng = np.random.Generator(np.random.PCG64(500 + S))
+    B, H, L = 2, 3, 2
+    pm = rng.standard_normal((B, H, L, S)).astype(np.float32) * 5.0
+    pl = (rng.random((B, H, L, S)).astype(np.float32) + 0.5) * 10.0
+    pacc = rng.standard_normal((B, H, L, S, d)).astype(np.float32) * 8.0
+    if S >= 3:                          # identity chunks in the middle and at the end
+        pm[:, :, :, 1] = -np.inf; pl[:, :, :, 1] = 0.0; pacc[:, :, :, 1] = 0.0
+        pm[0, 0, 0, -1] = -np.inf; pl[0, 0, 0, -1] = 0.0; pacc[0, 0, 0, -1] = 0.0
+    pm[1, 2, 1, :] = -np.inf; pl[1, 2, 1, :] = 0.0; pacc[1, 2, 1, :] = 0.0     # a row with nothing visible
+    o = torch.empty((B, H, L, d), dtype=torch.float32 if out_dtype == "f32" else torch.bfloat16, device=DEV)
+    rf.rf_merge_states(*(torch.from_numpy(a).to(DEV) for a in (pm, pl, pacc)), o)
+    torch.cuda.synchronize()
+    ref = O.merge_states(pm, pl, pacc)
+    assert np.all(ref[1, 2, 1] == 0.0)
+    check(o, ref, out_dtype, "merge")
+
+
+# --------------------------------------------------------- RMSNorm + linear
+@pytest.mark.parametrize("M,K,N", [(128, 256, 128), (77, 64, 72), (300, 512, 264), (1, 128, 8), (256, 1024, 384)])
+def test_rmsnorm_gemm_shapes(rf, M, K, N):
+    say(f"rmsnorm_gemm M{M} K{K} N{N}")
+    x, g, w = I.rmsnorm_gemm_inputs(I.SEED_BASE + 4, M, K, N)
+    y = rf.rf_rmsnorm_gemm(*(I.to_torch(a, "bf16", DEV) for a in (x, g, w)), eps=1e-6)
+    torch.cuda.synchronize()
+    check(y, O.rmsnorm_gemm(x, g, w, 1e-6), "bf16", "rmsnorm_gemm")
+
+
+def test_rmsnorm_gemm_row_scales_and_pitched_output(rf):
+    say("rmsnorm_gemm rows of very different norm, pitched y")
+    M, K, N = 64, 256, 128
+    x, g, w = I.rmsnorm_gemm_inputs(91, M, K, N)
+    x[0] = I.bf16_round(x[0] * 1e-3)       # tiny row: eps matters
+    x[1] = I.bf16_round(x[1] * 300.0)      # huge row
+    x[2] = 0.0                             # zero row -> zeros
+    x[2, 5] = 0.0
+    ybig = torch.zeros((M, 2 * N), dtype=torch.bfloat16, device=DEV)
+    rf.rf_rmsnorm_gemm(*(I.to_torch(a, "bf16", DEV) for a in (x, g, w)), eps=1e-6, y=ybig[:, N:])
+    torch.cuda.synchronize()
+    ref = O.rmsnorm_gemm(x, g, w, 1e-6)
+    check(ybig[:, N:], ref, "bf16", "rmsnorm_gemm pitched")
+    assert float(ybig[:, :N].abs().max()) == 0.0
+    # per-row check so that the small row is not hidden by the large ones
+    out = I.to_numpy(ybig[:, N:])
+    for i in (0, 1, 3):
+        assert np.max(np.abs(out[i] - ref[i])) <= 2e-2 * np.max(np.abs(ref[i]))
+    assert np.all(out[2] == 0.0)

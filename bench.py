@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the cascaded-reduction hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+input: every entry point of the library on its benchmark workload
+  w0  rf_cascade_attention         fp32  Q[128,64] K,V[512,64]
+  w1  rf_safe_softmax              bf16  X[32768,4096]
+  w2  rf_cascade_attention         bf16  B4 H32 L2048 d128, non-causal and causal
+  w3  rf_cascade_attention_splitk + rf_merge_states   bf16 B16 Hq32 Hkv8 Lk32768 d128, S=64
+  w4  rf_rmsnorm_gemm              bf16  4096 x 4096 x 4096
+Inputs are generated on the device from fixed seeds before the timed region.
+The memory-bound workloads (w1, w3) rotate over three buffer sets so that the
+last-level cache cannot serve repeated reads.
+
+Prints ONE JSON line.  ``value`` is the fused-attention throughput of the
+prefill workload (non-causal), from the HIP-event time of that kernel inside
+the timed region; ``workloads`` carries every workload's time, throughput and
+roofline fraction; ``roofline`` is the kernel that takes the most time in a
+step; ``cpu_baseline`` times the fp64 oracle on a bounded sample of the
+prefill workload on the host cores.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA, published
+PEAK_F32_TFLOPS = 157.3        # fp32 matrix / vector, published
+N_ROT = 3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--only", type=str, default="", help="comma list of w0..w4 (profiling aid); default all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_10026_amd import binding as rf
+    from paper_2603_10026_amd import inputs as I
+
+    rf.load_library()                      # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4"}
+    W = I.WORKLOADS
+    seed = lambda i: I.SEED_BASE + i
+
+    # ---------------------------------------------------------------- inputs
+    state = {}
+    if "w0" in only:
+        c = W[0]
+        q, k, v = I.attention_inputs_device(seed(0), c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "f32", dev)
+        state["w0"] = dict(q=q, k=k, v=v, o=torch.empty_like(q), scale=I.default_scale(c["d"]))
+    if "w1" in only:
+        c = W[1]
+        xs = [I.softmax_inputs_device(seed(1) + 100 * r, c["rows"], c["n"], c["sigma"], "bf16", dev) for r in range(N_ROT)]
+        state["w1"] = dict(x=xs, y=[torch.empty_like(x) for x in xs])
+    if "w2" in only:
+        c = W[2]
+        q, k, v = I.attention_inputs_device(seed(2), c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "bf16", dev)
+        state["w2"] = dict(q=q, k=k, v=v, o=torch.empty_like(q), oc=torch.empty_like(q), scale=I.default_scale(c["d"]))
+    if "w3" in only:
+        c = W[3]
+        sets = []
+        for r in range(N_ROT):
+            q, k, v = I.attention_inputs_device(seed(3) + 100 * r, c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "bf16", dev)
+            pm, pl, pacc = rf.alloc_partial_states(q, c["num_splits"])
+            sets.append(dict(q=q, k=k, v=v, pm=pm, pl=pl, pacc=pacc, o=torch.empty_like(q)))
+        state["w3"] = dict(sets=sets, scale=I.default_scale(c["d"]), S=c["num_splits"])
+    if "w4" in only:
+        c = W[4]
+        x, g, w = I.rmsnorm_gemm_inputs_device(seed(4), c["M"], c["K"], c["N"], c["w_sigma"], "bf16", dev)
+        state["w4"] = dict(x=x, g=g, w=w, y=torch.empty((c["M"], c["N"]), dtype=torch.bfloat16, device=dev), eps=c["eps"])
+    torch.cuda.synchronize()
+
+    # kernels of one step, in launch order: (label, callable(step_index))
+    launches = []
+    if "w0" in only:
+        s0 = state["w0"]
+        launches.append(("w0_attention_f32", lambda i: rf.rf_cascade_attention(s0["q"], s0["k"], s0["v"], s0["scale"], False, o=s0["o"])))
+    if "w1" in only:
+        s1 = state["w1"]
+        launches.append(("w1_softmax", lambda i: rf.rf_safe_softmax(s1["x"][i % N_ROT], s1["y"][i % N_ROT])))
+    if "w2" in only:
+        s2 = state["w2"]
+        launches.append(("w2_attention_prefill", lambda i: rf.rf_cascade_attention(s2["q"], s2["k"], s2["v"], s2["scale"], False, o=s2["o"])))
+        launches.append(("w2_attention_prefill_causal", lambda i: rf.rf_cascade_attention(s2["q"], s2["k"], s2["v"], s2["scale"], True, o=s2["oc"])))
+    if "w3" in only:
+        s3 = state["w3"]
+
+        def splitk(i):
+            t = s3["sets"][i % N_ROT]
+            rf.rf_cascade_attention_splitk(t["q"], t["k"], t["v"], s3["S"], t["pm"], t["pl"], t["pacc"], s3["scale"], False)
+
+        def merge(i):
+            t = s3["sets"][i % N_ROT]
+            rf.rf_merge_states(t["pm"], t["pl"], t["pacc"], t["o"])
+
+        launches.append(("w3_decode_splitk", splitk))
+        launches.append(("w3_decode_merge", merge))
+    if "w4" in only:
+        s4 = state["w4"]
+        launches.append(("w4_rmsnorm_gemm", lambda i: rf.rf_rmsnorm_gemm(s4["x"], s4["g"], s4["w"], s4["eps"], y=s4["y"])))
+
+    def run_step(i, events=None):
+        for j, (_, fn) in enumerate(launches):
+            if events is not None:
+                events[j][0].record()
+            fn(i)
+            if events is not None:
+                events[j][1].record()
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in launches]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_step(args.warmup + i, ev[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # average kernel duration per launch over the timed region (HIP events on the launch stream)
+    dur_us = {}
+    for j, (label, _) in enumerate(launches):
+        ts = [ev[i][j][0].elapsed_time(ev[i][j][1]) * 1e3 for i in range(args.steps)]
+        dur_us[label] = dict(avg=float(np.mean(ts)), med=float(np.median(ts)), min=float(np.min(ts)))
+
+    # ---------------------------------------------- algorithmic work per launch
+    def attn_flops(c, causal):
+        pairs = c["Lq"] * (c["Lq"] + 1) // 2 if causal else c["Lq"] * c["Lk"]
+        return 4.0 * c["B"] * c["Hq"] * pairs * c["d"]
+
+    work = {}
+    c = W[0]
+    work["w0_attention_f32"] = dict(bound="latency", flops=attn_flops(c, False),
+                                    bytes=4.0 * (2 * c["Lq"] * c["d"] + 2 * c["Lk"] * c["d"]))
+    c = W[1]
+    work["w1_softmax"] = dict(bound="hbm", bytes=2.0 * c["rows"] * c["n"] * 2)
+    c = W[2]
+    work["w2_attention_prefill"] = dict(bound="mfma", flops=attn_flops(c, False))
+    work["w2_attention_prefill_causal"] = dict(bound="mfma", flops=attn_flops(c, True))
+    c = W[3]
+    kv_bytes = 2.0 * c["B"] * c["Hkv"] * c["Lk"] * c["d"] * 2
+    part_bytes = 1.0 * c["B"] * c["Hq"] * c["Lq"] * c["num_splits"] * (c["d"] + 2) * 4
+    qo_bytes = 2.0 * c["B"] * c["Hq"] * c["Lq"] * c["d"] * 2
+    work["w3_decode_splitk"] = dict(bound="hbm", bytes=kv_bytes + part_bytes + qo_bytes / 2)
+    work["w3_decode_merge"] = dict(bound="hbm", bytes=part_bytes + qo_bytes / 2)
+    c = W[4]
+    work["w4_rmsnorm_gemm"] = dict(bound="mfma", flops=2.0 * c["M"] * c["K"] * c["N"],
+                                   bytes=2.0 * (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] + c["K"]))
+
+    workloads = {}
+    rooflines = []
+    for label, _ in launches:
+        wk, d = work[label], dur_us[label]
+        sec = d["avg"] * 1e-6
+        entry = dict(us_avg=round(d["avg"], 2), us_med=round(d["med"], 2), us_min=round(d["min"], 2), bound=wk["bound"])
+        if wk["bound"] == "hbm":
+            ach = wk["bytes"] / sec / 1e9
+            entry.update(GBps=round(ach, 1), frac=round(ach / PEAK_HBM_GBS, 4), algorithmic_bytes=wk["bytes"])
+            rooflines.append(dict(kernel=label, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                                  frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, us=round(d["avg"], 2)))
+        elif wk["bound"] == "mfma":
+            ach = wk["flops"] / sec / 1e12
+            entry.update(TFLOPs=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4), algorithmic_flops=wk["flops"])
+            rooflines.append(dict(kernel=label, bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
+                                  unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                                  us=round(d["avg"], 2)))
+        else:
+            entry.update(TFLOPs=round(wk["flops"] / sec / 1e12, 3), note="launch-latency bound; time is the figure of merit")
+        workloads[label] = entry
+    # decode = split kernel + merge kernel together
+    if "w3" in only:
+        tot = (dur_us["w3_decode_splitk"]["avg"] + dur_us["w3_decode_merge"]["avg"]) * 1e-6
+        b = work["w3_decode_splitk"]["bytes"] + work["w3_decode_merge"]["bytes"]
+        workloads["w3_decode_total"] = dict(us_avg=round(tot * 1e6, 2), GBps=round(b / tot / 1e9, 1),
+                                            frac=round(b / tot / 1e9 / PEAK_HBM_GBS, 4), bound="hbm", algorithmic_bytes=b)
+
+    dominant = max(rooflines, key=lambda r: r["us"]) if rooflines else None
+
+    # ------------------------------------------------------------ cpu baseline
+    cpu = None
+    if not args.no_cpu_baseline and "w2" in only:
+        from oracle import rf_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        c = W[2]
+        s2 = state["w2"]
+        nh = 16                                  # heads of batch 0: a bounded sample of the same workload
+        qh, kh, vh = (I.to_numpy(t[:1, :nh]) for t in (s2["q"], s2["k"], s2["v"]))
+        tc0 = time.perf_counter()
+        ref = O.attention(qh, kh, vh, s2["scale"], False)
+        tc1 = time.perf_counter()
+        fl = 4.0 * nh * c["Lq"] * c["Lk"] * c["d"]
+        got = I.to_numpy(s2["o"][:1, :nh])
+        err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        cpu = dict(value=round(fl / (tc1 - tc0) / 1e12, 5), unit="TFLOP/s", cores=int(cores), kind="oracle",
+                   sample=f"{nh} of {c['B'] * c['Hq']} heads of the non-causal prefill workload, fp64 numpy, {tc1 - tc0:.1f} s",
+                   gpu_vs_oracle_max_err_over_max_ref=err)
+
+    primary = workloads.get("w2_attention_prefill")
+    out = {
+        "metric": "fused-attention TFLOP/s (bf16 prefill, non-causal); softmax/decode GB/s and % of roofline per workload in `workloads`",
+        "value": primary["TFLOPs"] if primary else None,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "attn_prefill_bf16_B4_H32_L2048_d128_noncausal (value); one step = all five workloads: "
+                               "attn_f32_128x512x64, softmax_bf16_32768x4096, prefill non-causal + causal, "
+                               "decode_gqa_B16_Hq32_Hkv8_Lk32768_S64 split+merge, rmsnorm_gemm_4096^3",
+                   "seeds": [I.SEED_BASE + i for i in range(5)]},
+        "workloads": workloads,
+        "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]} if dominant else None,
+        "rooflines": rooflines,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

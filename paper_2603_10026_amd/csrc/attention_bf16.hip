@@ -8,16 +8,28 @@
 // max -> sum-exp -> weighted-sum cascade.  acc stays unnormalised (Eq. (8))
 // and is divided by l once in the epilogue.
 //
-//   S^T = K Q^T        A = K tile (LDS, XOR-swizzled rows), B = Q^T (registers)
-//   O^T += V^T P^T     A = V^T tile (LDS, transposed while staging), B = P^T
+//   S^T = K Q^T        A = K tile (LDS), B = Q^T (registers, loaded once)
+//   O^T += V^T P^T     A = V^T (LDS transpose reads of the V tile), B = P^T
 //
 // Computing the scores transposed makes the accumulator layout of S^T (lane =
 // query column, registers = key rows) coincide with the B-operand layout of
 // the second product, so probabilities go from fp32 accumulators to bf16
-// operands without leaving their lane.  The key order inside each 16-key group
-// is permuted identically on both operands of the second product (a sum over
-// keys does not care), which lets each lane fetch its eight keys of V^T with a
-// single 128-bit LDS read.
+// operands without leaving their lane.
+//
+// Data movement: K and V tiles go from HBM straight into LDS with 128-bit
+// direct-to-LDS loads (no staging registers), double-buffered, one barrier per
+// tile.  Rows are XOR-swizzled in 16-byte slots so that both the 128-bit
+// A-operand reads of K and the 64-bit transpose reads of V are free of bank
+// conflicts.  Two workgroups fit on a compute unit, so the softmax VALU work
+// of one overlaps the MFMA work of the other.
+//
+// The reference point m of the state is only advanced when a tile's row max
+// exceeds it by more than kTau (in log2 units): (m, l, acc) with any common
+// reference gives the same O = acc / l, exponentials stay below 2^kTau, and
+// the rescale of acc (the correction step of the incremental form) is skipped
+// on almost every tile.
+#include <type_traits>
+
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -29,46 +41,44 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * kWave;
 constexpr int kBQ = 128;  // query rows per workgroup
 constexpr int kBK = 64;   // keys per tile
+constexpr float kTau = 8.0f;
 
-__device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
-  return __builtin_amdgcn_perm(y, x, 0x05040100u);
-}
-__device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
-  return __builtin_amdgcn_perm(y, x, 0x07060302u);
-}
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_cvoid;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 
-// K tile in LDS: row = key (D bf16), 16-byte pieces XOR-swizzled by row.
+// 16-byte slot swizzles (slot = piece ^ f(row)).
 template <int D>
-__device__ __forceinline__ int k_lds_off(int row, int piece) {
-  constexpr int P = D / 8;  // pieces per row
-  const int f = (P == 16) ? (row & 15) : ((row >> 1) & 7);
-  return row * (D * 2) + (((piece ^ f) & (P - 1)) << 4);
+__device__ __forceinline__ int fK(int row) {
+  return (D == 128) ? (row & 15) : ((row >> 1) & 7);
 }
-// V^T tile in LDS: row = head-dim index (64 key slots, 128 bytes), 16-byte
-// granules XOR-swizzled by row.  Slot order inside a 16-key group: bits 2 and 3
-// of the key index are swapped.
-__device__ __forceinline__ int vt_lds_off(int d, int granule) {
-  const int f = ((d >> 1) ^ (d >> 4)) & 7;
-  return d * (kBK * 2) + ((granule ^ f) << 4);
+template <int D>
+__device__ __forceinline__ int fV(int row) {
+  return (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3))
+                    : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+__device__ __forceinline__ void wait_vmem_all() {
+  // vmcnt(0), expcnt and lgkmcnt untouched (gfx9 encoding)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
 }  // namespace
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void attention_bf16_kernel(
+__global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     bf16_t* __restrict__ o, Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so, int Hq, int Hkv,
     int Lq, int Lk, float scale_log2e, int causal, int n_qtiles) {
-  constexpr int KS = D / 16;   // contraction steps of S^T = K Q^T
-  constexpr int DT = D / 32;   // 32-row tiles of O^T
-  constexpr int P = D / 8;     // 16-byte pieces per K/V row
-  constexpr int KLD = kBK * P / kThreads;       // K loads per thread per tile
-  constexpr int VROWS = 4;                      // keys per thread in the V transpose
-  constexpr int NVB = (kBK / VROWS) * P;        // 4-key x 8-column V blocks per tile
-  constexpr int VBLK = (NVB + kThreads - 1) / kThreads;  // V blocks per thread per tile
+  constexpr int KS = D / 16;                 // contraction steps of S^T = K Q^T
+  constexpr int DT = D / 32;                 // 32-row tiles of O^T
+  constexpr int P = D / 8;                   // 16-byte slots per K/V row
+  constexpr int ROWB = D * 2;                // bytes per K/V row
+  constexpr int TILEB = kBK * ROWB;          // bytes per K or V tile
+  constexpr int ROWS_PER_LD = 1024 / ROWB;   // rows covered by one wavefront load
+  constexpr int LD_PER_WAVE = kBK / ROWS_PER_LD / kWaves;
 
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[kBK * D * 2];
-  __shared__ __attribute__((aligned(16))) unsigned char vt_lds[D * kBK * 2];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * TILEB];  // [buf][K,V]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -76,9 +86,15 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(
   const int i32 = lane & 31;
   const int hh = lane >> 5;
 
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
+  // them so that an XCD receives consecutive ids: the query tiles of one head then
+  // share that head's K/V in one L2, and every XCD gets the same mix of heavy and
+  // light tiles under a causal mask.
+  int vid = blockIdx.x;
+  if ((gridDim.x & 7) == 0) vid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   // heavy (late) query tiles first: under a causal mask they have the most keys
-  const int qt = n_qtiles - 1 - (int)(blockIdx.x % n_qtiles);
-  const int bh = blockIdx.x / n_qtiles;
+  const int qt = n_qtiles - 1 - (vid % n_qtiles);
+  const int bh = vid / n_qtiles;
   const int h = bh % Hq;
   const int b = bh / Hq;
   const int hk = h / (Hq / Hkv);
@@ -96,6 +112,18 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const u32x4*>(qp + 16 * kk);
   }
+  // The loop below needs a positive scale (row max taken on raw scores, masked
+  // scores set to -inf before scaling): fold the sign of the scale into Q, and
+  // turn scale == 0 (uniform weights) into Q = 0 with scale 1.
+  if (scale_log2e < 0.f) {
+    scale_log2e = -scale_log2e;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] ^= 0x80008000u;
+  } else if (scale_log2e == 0.f) {
+    scale_log2e = 1.0f;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = u32x4{0u, 0u, 0u, 0u};
+  }
 
   const int shift = Lk - Lq;
   const int my_last = causal ? min(Lk - 1, my_q + shift) : Lk - 1;
@@ -104,141 +132,191 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(
   const int wg_last = causal ? min(Lk - 1, min(Lq - 1, q0 + kBQ - 1) + shift) : Lk - 1;
   const int n_ktiles = wg_last >= 0 ? wg_last / kBK + 1 : 0;
 
-  float m2 = -INFINITY, l = 0.f;
+  // ---- direct-to-LDS load geometry: this lane's row / slot in each of its loads ----
+  int ld_row[LD_PER_WAVE];
+  int ld_kcol[LD_PER_WAVE], ld_vcol[LD_PER_WAVE];  // element offsets inside the global row
+  uint32_t ld_koff[LD_PER_WAVE], ld_voff[LD_PER_WAVE];  // byte offsets from the tile's first row
+#pragma unroll
+  for (int e = 0; e < LD_PER_WAVE; ++e) {
+    const int inst = wave * LD_PER_WAVE + e;
+    const int row = inst * ROWS_PER_LD + lane / P;
+    const int slot = lane % P;
+    ld_row[e] = row;
+    ld_kcol[e] = 8 * (slot ^ fK<D>(row));
+    ld_vcol[e] = 8 * (slot ^ fV<D>(row));
+    ld_koff[e] = (uint32_t)(((int64_t)row * sk.l + ld_kcol[e]) * 2);
+    ld_voff[e] = (uint32_t)(((int64_t)row * sv.l + ld_vcol[e]) * 2);
+  }
+  // byte offsets stay below 2^32 inside one 64-row tile only if the row stride does
+  const bool small_stride = sk.l < (1 << 24) && sv.l < (1 << 24);
+  auto issue_loads = [&](int key0, int buf) {
+    unsigned char* kdst = lds + buf * 2 * TILEB;
+    unsigned char* vdst = kdst + TILEB;
+    if (key0 + kBK <= Lk && small_stride) {
+      // full tile: uniform tile base + per-lane 32-bit offset, no per-load address math
+      const char* ktile = reinterpret_cast<const char*>(kb) + (int64_t)key0 * sk.l * 2;
+      const char* vtile = reinterpret_cast<const char*>(vb) + (int64_t)key0 * sv.l * 2;
+#pragma unroll
+      for (int e = 0; e < LD_PER_WAVE; ++e) {
+        const int inst = wave * LD_PER_WAVE + e;
+        __builtin_amdgcn_global_load_lds((global_cvoid*)(ktile + ld_koff[e]),
+                                         (lds_void*)(kdst + inst * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cvoid*)(vtile + ld_voff[e]),
+                                         (lds_void*)(vdst + inst * 1024), 16, 0, 0);
+      }
+    } else {
+      // ragged last tile: rows past the end re-read the last key (masked later)
+#pragma unroll
+      for (int e = 0; e < LD_PER_WAVE; ++e) {
+        const int inst = wave * LD_PER_WAVE + e;
+        const int key = min(key0 + ld_row[e], Lk - 1);
+        const bf16_t* ksrc = kb + (int64_t)key * sk.l + ld_kcol[e];
+        const bf16_t* vsrc = vb + (int64_t)key * sv.l + ld_vcol[e];
+        __builtin_amdgcn_global_load_lds((global_cvoid*)ksrc, (lds_void*)(kdst + inst * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cvoid*)vsrc, (lds_void*)(vdst + inst * 1024), 16, 0, 0);
+      }
+    }
+  };
+
+  // ---- LDS read offsets (loop invariant) ----
+  int koff[KS];  // + rt * 32 * ROWB
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) koff[kk] = i32 * ROWB + (((2 * kk + hh) ^ fK<D>(i32)) << 4);
+  // transpose reads of V: lane = 32hh + 16g2 + 4j + a reads 8 bytes of key row
+  // (16u + 8w + 4hh + j) at head-dim offset 32t + 16g2 + 4a; the 16-lane group gets,
+  // in lane 4a + e, keys j = 0..3 of head-dim 32t + 16g2 + 4a + e.
+  int voff[DT][2];  // + u * 16 * ROWB
+  {
+    const int i16 = lane & 15, g2 = (lane >> 4) & 1;
+    const int j = i16 >> 2, a = i16 & 3;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int w2 = 0; w2 < 2; ++w2) {
+        const int row = 8 * w2 + 4 * hh + j;
+        const int piece = 4 * t + 2 * g2 + (a >> 1);
+        voff[t][w2] = row * ROWB + (((piece ^ fV<D>(row)) & (P - 1)) << 4) + 8 * (a & 1);
+      }
+  }
+
+  float m_ref = -INFINITY, l = 0.f;
   f32x16 acc[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-  // staging registers
-  u32x4 kreg[KLD];
-  u32x4 vreg[VBLK][VROWS];
+  const uint32_t lds_base =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+#pragma unroll
+  for (int t = 0; t < DT; ++t) { voff[t][0] += lds_base; voff[t][1] += lds_base; }
 
-  auto load_tile = [&](int key0) {
-#pragma unroll
-    for (int e = 0; e < KLD; ++e) {
-      const int idx = e * kThreads + tid;
-      const int row = idx / P, piece = idx % P;
-      const int key = min(key0 + row, Lk - 1);
-      kreg[e] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * sk.l + 8 * piece);
-    }
-#pragma unroll
-    for (int e = 0; e < VBLK; ++e) {
-      const int idx = e * kThreads + tid;
-      if (idx >= NVB) break;
-      const int jg = idx / P, piece = idx % P;  // jg: group of 4 consecutive keys
-#pragma unroll
-      for (int rr = 0; rr < VROWS; ++rr) {
-        const int key = min(key0 + 4 * jg + rr, Lk - 1);
-        vreg[e][rr] = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * sv.l + 8 * piece);
-      }
-    }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int e = 0; e < KLD; ++e) {
-      const int idx = e * kThreads + tid;
-      const int row = idx / P, piece = idx % P;
-      *reinterpret_cast<u32x4*>(k_lds + k_lds_off<D>(row, piece)) = kreg[e];
-    }
-#pragma unroll
-    for (int e = 0; e < VBLK; ++e) {
-      const int idx = e * kThreads + tid;
-      if (idx >= NVB) break;
-      const int jg = idx / P, piece = idx % P;
-      // slot of key 4jg + rr inside its 16-key group: swap bits 2 and 3
-      const int slot0 = 16 * (jg >> 2) + 8 * (jg & 1) + 4 * ((jg >> 1) & 1);
-      const int granule = slot0 >> 3;
-      const int half = (slot0 >> 2) & 1;
-#pragma unroll
-      for (int tp = 0; tp < 4; ++tp) {
-        // 4 keys x 2 head-dim columns -> two 8-byte rows of V^T
-        u32x2 lo2, hi2;
-        lo2[0] = pair_lo(vreg[e][0][tp], vreg[e][1][tp]);
-        lo2[1] = pair_lo(vreg[e][2][tp], vreg[e][3][tp]);
-        hi2[0] = pair_hi(vreg[e][0][tp], vreg[e][1][tp]);
-        hi2[1] = pair_hi(vreg[e][2][tp], vreg[e][3][tp]);
-        const int d0 = 8 * piece + 2 * tp;
-        *reinterpret_cast<u32x2*>(vt_lds + vt_lds_off(d0, granule) + 8 * half) = lo2;
-        *reinterpret_cast<u32x2*>(vt_lds + vt_lds_off(d0 + 1, granule) + 8 * half) = hi2;
-      }
-    }
-  };
-
-  if (n_ktiles > 0) load_tile(0);
-  for (int kt = 0; kt < n_ktiles; ++kt) {
+  // One key tile.  BUF is a compile-time constant so that every LDS access of the
+  // tile is a loop-invariant register plus an immediate offset.
+  auto tile_step = [&](int kt, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
     const int key0 = kt * kBK;
-    __syncthreads();  // previous tile's LDS reads are done
-    store_tile();
-    __syncthreads();
-    if (kt + 1 < n_ktiles) load_tile(key0 + kBK);
-    if (key0 > wave_last) continue;  // nothing visible for this wavefront (uniform)
+    wait_vmem_all();   // this wavefront's share of tile kt has landed
+    __syncthreads();   // everyone's share has landed; everyone is done reading the other buffer
+    if (kt + 1 < n_ktiles) issue_loads(key0 + kBK, BUF ^ 1);
+    if (key0 > wave_last) return;  // nothing visible for this wavefront (uniform)
+
+    const unsigned char* kt_lds = lds + BUF * 2 * TILEB;
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
     f32x16 s[2];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[rt][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        const u32x4 a =
-            *reinterpret_cast<const u32x4*>(k_lds + k_lds_off<D>(32 * rt + i32, 2 * kk + hh));
+    for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(kt_lds + koff[kk] + rt * 32 * ROWB);
         s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                         __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
                                                         0, 0, 0);
       }
     }
-    // s[rt][r] = score(key key0 + 32rt + 8(r/4) + 4hh + r%4, query my_q)
-    const bool need_mask = key0 + kBK - 1 > wave_min_last;  // uniform per wavefront
+    // s[rt][r] = raw score(key key0 + 32rt + 8(r/4) + 4hh + r%4, query my_q)
+    if (key0 + kBK - 1 > wave_min_last) {  // uniform: tile crosses the mask boundary
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + 32 * rt + 8 * (r >> 2) + 4 * hh + (r & 3);
+          s[rt][r] = (key <= my_last) ? s[rt][r] : -INFINITY;
+        }
+    }
+    // ---- stage 1: running max (reference point advanced lazily) ----
     float tmax = -INFINITY;
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[rt][r] * scale_log2e;
-        if (need_mask) {
-          const int key = key0 + 32 * rt + 8 * (r >> 2) + 4 * hh + (r & 3);
-          x = (key <= my_last) ? x : -INFINITY;
-        }
-        s[rt][r] = x;
-        tmax = fmaxf(tmax, x);
-      }
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[rt][r]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    // ---- stage 1: running max; stage 2: running sum of exponentials ----
-    const float m_new = fmaxf(m2, tmax);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float corr = fast_exp2(m2 - m_use);
-    m2 = m_new;
+    const float tmax2 = tmax * scale_log2e;  // log2 units; scale > 0 keeps the order
+    if (__builtin_amdgcn_ballot_w64(tmax2 > m_ref + kTau) != 0) {
+      const float m_new = fmaxf(m_ref, tmax2);
+      const float corr = (m_new == -INFINITY) ? 1.0f : fast_exp2(m_ref - m_new);
+      m_ref = m_new;
+      l *= corr;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] *= corr;
+    }
+    // ---- stage 2: running sum of exponentials; P^T packed to bf16 B operands ----
+    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
     float psum = 0.f;
-    u32x4 pb[4];  // B operands of the 4 contraction steps (16 keys each)
+    u32x4 pb[4];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r2 = 0; r2 < 8; ++r2) {
-        const float p0 = fast_exp2(s[rt][2 * r2] - m_use);
-        const float p1 = fast_exp2(s[rt][2 * r2 + 1] - m_use);
+        const float p0 = fast_exp2(fmaf(s[rt][2 * r2], scale_log2e, neg_m));
+        const float p1 = fast_exp2(fmaf(s[rt][2 * r2 + 1], scale_log2e, neg_m));
         psum += p0 + p1;
         pb[2 * rt + (r2 >> 2)][r2 & 3] = pack_bf16(p0, p1);
       }
-    l = l * corr + psum;
-    // ---- stage 3: acc = acc * corr + V^T P^T ----
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[t][r] *= corr;
+    l += psum;
+    // ---- stage 3: acc += V^T P^T ----
+    // The transpose reads are issued as raw instructions and waited for by hand:
+    // going through the compiler's intrinsic would make it wait for the
+    // direct-to-LDS loads of the NEXT tile before every read of this one.
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
+      u32x2 va[DT][2];
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int w2 = 0; w2 < 2; ++w2)
+          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                       : "=v"(va[t][w2])
+                       : "v"(voff[t][w2]), "n"(BUF * 2 * TILEB + TILEB + u * 16 * ROWB));
+      if constexpr (DT == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]),
+                       "+v"(va[2][0]), "+v"(va[2][1]), "+v"(va[3][0]), "+v"(va[3][1]));
+      else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]));
 #pragma unroll
       for (int t = 0; t < DT; ++t) {
-        const u32x4 a =
-            *reinterpret_cast<const u32x4*>(vt_lds + vt_lds_off(32 * t + i32, 2 * u + hh));
+        u32x4 a;
+        a[0] = va[t][0][0]; a[1] = va[t][0][1]; a[2] = va[t][1][0]; a[3] = va[t][1][1];
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                          __builtin_bit_cast(bf16x8, pb[u]), acc[t],
                                                          0, 0, 0);
       }
     }
+  };
+
+  if (n_ktiles > 0) issue_loads(0, 0);
+  for (int kt = 0; kt < n_ktiles; kt += 2) {
+    tile_step(kt, std::integral_constant<int, 0>{});
+    if (kt + 1 < n_ktiles) tile_step(kt + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: O = acc / l ----

@@ -224,20 +224,35 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     const unsigned char* kt_lds = lds + BUF * 2 * TILEB;
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
+    // The K fragments of contraction steps 2i, 2i+1 are fetched while the MFMAs of
+    // steps 2i-2, 2i-1 run (two-stage register pipeline).
     f32x16 s[2];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[rt][r] = 0.f;
+    u32x4 kf[2][4];
+    auto load_kf = [&](int stage, int step) {
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(kt_lds + koff[kk] + rt * 32 * ROWB);
-        s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                        __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
-                                                        0, 0, 0);
-      }
+        for (int rt = 0; rt < 2; ++rt)
+          kf[stage][2 * c + rt] =
+              *reinterpret_cast<const u32x4*>(kt_lds + koff[2 * step + c] + rt * 32 * ROWB);
+    };
+    load_kf(0, 0);
+#pragma unroll
+    for (int step = 0; step < KS / 2; ++step) {
+      if (step + 1 < KS / 2) load_kf((step + 1) & 1, step + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+          s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, kf[step & 1][2 * c + rt]),
+              __builtin_bit_cast(bf16x8, qf[2 * step + c]), s[rt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // s[rt][r] = raw score(key key0 + 32rt + 8(r/4) + 4hh + r%4, query my_q)
     if (key0 + kBK - 1 > wave_min_last) {  // uniform: tile crosses the mask boundary
@@ -285,32 +300,52 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     // The transpose reads are issued as raw instructions and waited for by hand:
     // going through the compiler's intrinsic would make it wait for the
     // direct-to-LDS loads of the NEXT tile before every read of this one.
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      u32x2 va[DT][2];
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int w2 = 0; w2 < 2; ++w2)
-          asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                       : "=v"(va[t][w2])
-                       : "v"(voff[t][w2]), "n"(BUF * 2 * TILEB + TILEB + u * 16 * ROWB));
-      if constexpr (DT == 4)
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]),
-                       "+v"(va[2][0]), "+v"(va[2][1]), "+v"(va[3][0]), "+v"(va[3][1]));
-      else
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]));
-#pragma unroll
-      for (int t = 0; t < DT; ++t) {
-        u32x4 a;
-        a[0] = va[t][0][0]; a[1] = va[t][0][1]; a[2] = va[t][1][0]; a[3] = va[t][1][1];
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                         __builtin_bit_cast(bf16x8, pb[u]), acc[t],
-                                                         0, 0, 0);
-      }
-    }
+    u32x2 va[2][DT][2];
+#define RF_ISSUE_V(STAGE, U)                                                              \
+  _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                        \
+    _Pragma("unroll") for (int w2 = 0; w2 < 2; ++w2) asm volatile(                        \
+        "ds_read_b64_tr_b16 %0, %1 offset:%2"                                             \
+        : "=v"(va[STAGE][t][w2])                                                          \
+        : "v"(voff[t][w2]), "n"(BUF * 2 * TILEB + TILEB + (U) * 16 * ROWB));              \
+  }
+    // wait until at most PENDING transpose reads are still in flight; the registers of
+    // STAGE are tied to the wait so that their uses stay behind it
+#define RF_WAIT_V(STAGE, PENDING)                                                         \
+  if constexpr (DT == 4)                                                                  \
+    asm volatile("s_waitcnt lgkmcnt(%8)"                                                  \
+                 : "+v"(va[STAGE][0][0]), "+v"(va[STAGE][0][1]), "+v"(va[STAGE][1][0]),   \
+                   "+v"(va[STAGE][1][1]), "+v"(va[STAGE][2][0]), "+v"(va[STAGE][2][1]),   \
+                   "+v"(va[STAGE][3][0]), "+v"(va[STAGE][3][1])                           \
+                 : "n"(PENDING));                                                         \
+  else                                                                                    \
+    asm volatile("s_waitcnt lgkmcnt(%4)"                                                  \
+                 : "+v"(va[STAGE][0][0]), "+v"(va[STAGE][0][1]), "+v"(va[STAGE][1][0]),   \
+                   "+v"(va[STAGE][1][1])                                                  \
+                 : "n"(PENDING));
+#define RF_PV_STEP(STAGE, U)                                                              \
+  _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                        \
+    u32x4 a;                                                                              \
+    a[0] = va[STAGE][t][0][0]; a[1] = va[STAGE][t][0][1];                                 \
+    a[2] = va[STAGE][t][1][0]; a[3] = va[STAGE][t][1][1];                                 \
+    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                     \
+        __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pb[U]), acc[t], 0, 0, 0); \
+  }
+    constexpr int NV = 2 * DT;  // transpose reads per contraction step
+    RF_ISSUE_V(0, 0)
+    RF_ISSUE_V(1, 1)
+    RF_WAIT_V(0, NV)
+    RF_PV_STEP(0, 0)
+    RF_ISSUE_V(0, 2)
+    RF_WAIT_V(1, NV)
+    RF_PV_STEP(1, 1)
+    RF_ISSUE_V(1, 3)
+    RF_WAIT_V(0, NV)
+    RF_PV_STEP(0, 2)
+    RF_WAIT_V(1, 0)
+    RF_PV_STEP(1, 3)
+#undef RF_ISSUE_V
+#undef RF_WAIT_V
+#undef RF_PV_STEP
   };
 
   if (n_ktiles > 0) issue_loads(0, 0);

@@ -7,11 +7,20 @@
 // MFMA (fp32 accumulate) while a side accumulator collects ss_i from the very
 // same X tile on its way to LDS; the epilogue applies H(ss_i) once per row.
 //
-// The product is computed transposed, Y^T = W^T (X g)^T, so that each lane of
-// the accumulator owns one output row i (one H(ss_i) per lane) and four
-// consecutive output columns per register group (8-byte stores).
-//   A operand = W^T tile: W rows are transposed in registers while staging.
-//   B operand = (X g) tile: x*g rounded to bf16 once, while staging.
+// Tiling.  One workgroup of 8 wavefronts owns a 256 x 256 output tile and walks
+// K in steps of 64 through double-buffered LDS (one barrier per step).  The
+// product is computed transposed, Y^T = W^T (X g)^T, so that each accumulator
+// lane owns one output row i (one H(ss_i) per lane) and four consecutive output
+// columns per register group.
+//   A operand = W^T: the W tile goes HBM -> LDS with direct-to-LDS 128-bit loads
+//               and is read back with 64-bit LDS transpose reads.
+//   B operand = (X g): x*g is rounded to bf16 once, in registers, on the way
+//               from HBM to LDS; x^2 is accumulated there too.
+// Each wavefront owns a 64 (n) x 128 (m) sub-tile: 8 MFMAs per 4 + 4 LDS
+// fragment reads, register double-buffered over the four 16-wide contraction
+// steps of a K step.
+#include <type_traits>
+
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -19,30 +28,27 @@ namespace rf {
 
 namespace {
 
-constexpr int kGWaves = 4;
+constexpr int kGWaves = 8;
 constexpr int kGThreads = kGWaves * kWave;
-constexpr int kBM = 128, kBN = 128, kBKK = 64;
+constexpr int kBM = 256, kBN = 256, kBKK = 64;
+constexpr int kXTileB = kBM * kBKK * 2;   // 32 KB, [m][k], 128-byte rows
+constexpr int kWTileB = kBKK * kBN * 2;   // 32 KB, [k][n], 512-byte rows
+constexpr int kStageB = kXTileB + kWTileB;
 
-__device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
-  return __builtin_amdgcn_perm(y, x, 0x05040100u);
-}
-__device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
-  return __builtin_amdgcn_perm(y, x, 0x07060302u);
-}
-// Tiles in LDS: 64 contraction slots (128 bytes) per row, 16-byte pieces
-// XOR-swizzled by row so that 16 consecutive rows hit all banks.
-__device__ __forceinline__ int tile_off(int row, int piece) {
-  return row * (kBKK * 2) + ((piece ^ ((row >> 1) & 7)) << 4);
-}
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_cvoid;
+
+// 16-byte slot swizzles (slot = piece ^ f(row)).
+__device__ __forceinline__ int fX(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int fW(int krow) { return (krow & 3) << 2; }
 
 }  // namespace
 
-__global__ __launch_bounds__(kGThreads) void rmsnorm_gemm_bf16_kernel(
+__global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ g, const bf16_t* __restrict__ w,
     bf16_t* __restrict__ y, int M, int K, int N, int64_t ldx, int64_t ldw, int64_t ldy,
-    float inv_k, float eps, int n_mtiles) {
-  __shared__ __attribute__((aligned(16))) unsigned char xs[kBM * kBKK * 2];   // (x g)[m][k]
-  __shared__ __attribute__((aligned(16))) unsigned char wts[kBN * kBKK * 2];  // w^T[n][k]
+    float inv_k, float eps, int n_mtiles, int n_ntiles) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStageB];
   __shared__ float s_rstd[kBM];
 
   const int tid = threadIdx.x;
@@ -50,111 +56,230 @@ __global__ __launch_bounds__(kGThreads) void rmsnorm_gemm_bf16_kernel(
   const int wave = tid >> 6;
   const int i32 = lane & 31;
   const int hh = lane >> 5;
-  const int wm = wave & 1;   // wavefront's 64-row half of the M tile
-  const int wn = wave >> 1;  // wavefront's 64-column half of the N tile
+  const int wn = wave & 3;   // 64-column block of the N tile
+  const int wm = wave >> 2;  // 128-row block of the M tile
 
-  const int mt = blockIdx.x % n_mtiles;
-  const int nt = blockIdx.x / n_mtiles;
+  // XCD-aware numbering: workgroups are dealt round-robin to 8 XCDs; give each XCD
+  // a run of consecutive tiles so that its L2 sees a few X row strips and W column
+  // strips many times instead of all of them once.
+  int vid = blockIdx.x;
+  if ((gridDim.x & 7) == 0) vid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  const int mt = vid / n_ntiles;
+  const int nt = vid % n_ntiles;
   const int m0 = mt * kBM, n0 = nt * kBN;
 
-  // staging roles
-  const int xpiece = tid & 7;    // 8 k-values of an X row
-  const int xrow = tid >> 3;     // + 32e, e = 0..3
-  const int wpiece = tid & 15;   // 8 n-values of a W row
-  const int wkg = tid >> 4;      // group of 4 consecutive k rows, 0..15
-  const int wn_src = min(n0 + 8 * wpiece, N - 8);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
-  f32x16 acc[2][2];  // [ni][mi]: Y^T tile (rows n, columns m)
+  // ---- X staging role: one half row (32 k-values) per thread ----
+  const int xrow = tid >> 1;
+  const int xhalf = tid & 1;
+  const bf16_t* xsrc = x + (int64_t)min(m0 + xrow, M - 1) * ldx + 32 * xhalf;
+  const bf16_t* gsrc = g + 32 * xhalf;
+  int xdst[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) xdst[c] = xrow * 128 + (((4 * xhalf + c) ^ fX(xrow)) << 4);
+
+  // ---- W direct-to-LDS role: 4 loads per wavefront per K step, 2 k-rows each ----
+  uint32_t wsrc_off[4];  // byte offset from w + k0*ldw (the tile's first row)
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int krow = 8 * wave + 2 * e + (lane >> 5);
+    const int piece = (lane & 31) ^ fW(krow);
+    const int ncol = min(n0 + 8 * piece, N - 8);
+    wsrc_off[e] = (uint32_t)(((int64_t)krow * ldw + ncol) * 2);
+  }
+  auto issue_w = [&](int k0, int buf) {
+    const char* wt = reinterpret_cast<const char*>(w) + (int64_t)k0 * ldw * 2;
+    unsigned char* dst = lds + buf * kStageB + kXTileB + wave * 4096;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      __builtin_amdgcn_global_load_lds((global_cvoid*)(wt + wsrc_off[e]), (lds_void*)(dst + e * 1024),
+                                       16, 0, 0);
+  };
+
+  // ---- fragment read addresses (LDS byte addresses, stage 0; + stage/step immediates) ----
+  // B operand (X g): lane (i32, hh) of column tile mi reads row 128wm + 32mi + i32, slot 2kk + hh
+  uint32_t xaddr[2][4];  // [stage][kk]; + mi * 32 * 128
+  {
+    const int row = 128 * wm + i32;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      xaddr[0][kk] = lds_base + row * 128 + (((2 * kk + hh) ^ fX(row)) << 4);
+      xaddr[1][kk] = xaddr[0][kk] + kStageB;
+    }
+  }
+  // A operand (W^T) by transpose reads: lane = 32hh + 16g2 + 4j + a reads 8 bytes of k-row
+  // 16kk + 8hh + 4w2 + j at column 64wn + 32ni + 16g2 + 4a
+  uint32_t waddr[2][2][2];  // [stage][ni][w2]; + kk * 16 * 512
+  {
+    const int i16 = lane & 15, g2 = (lane >> 4) & 1;
+    const int j = i16 >> 2, a = i16 & 3;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int w2 = 0; w2 < 2; ++w2) {
+        const int krow = 8 * hh + 4 * w2 + j;
+        const int piece = (64 * wn + 32 * ni + 16 * g2 + 4 * a) >> 3;
+        waddr[0][ni][w2] =
+            lds_base + kXTileB + krow * 512 + ((piece ^ fW(krow)) << 4) + 8 * (a & 1);
+        waddr[1][ni][w2] = waddr[0][ni][w2] + kStageB;
+      }
+  }
+
+  f32x16 acc[2][4];  // [ni][mi]: Y^T tile (rows n, columns m)
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
-  float ss[4] = {0.f, 0.f, 0.f, 0.f};
+  float ss = 0.f;
 
-  u32x4 xreg[4], wreg[4], greg;
-  auto load_tiles = [&](int k0) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int row = min(m0 + xrow + 32 * e, M - 1);
-      xreg[e] = *reinterpret_cast<const u32x4*>(x + (int64_t)row * ldx + k0 + 8 * xpiece);
-    }
-    greg = *reinterpret_cast<const u32x4*>(g + k0 + 8 * xpiece);
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr)
-      wreg[rr] = *reinterpret_cast<const u32x4*>(w + (int64_t)(k0 + 4 * wkg + rr) * ldw + wn_src);
+  // X and g tiles travel through registers.  Their loads are raw instructions with
+  // hand-placed waits: all vector-memory traffic of the main loop is ordered by hand
+  // so that the prefetches stay in flight across barriers.
+  u32x4 xreg[4], greg[4];
+  auto load_x = [&](int k0) {
+    const bf16_t* xp = xsrc + k0;
+    const bf16_t* gp = gsrc + k0;
+#define RF_LD(DST, PTR, OFF) \
+  asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(DST) : "v"(PTR), "n"(OFF));
+    RF_LD(xreg[0], xp, 0) RF_LD(xreg[1], xp, 16) RF_LD(xreg[2], xp, 32) RF_LD(xreg[3], xp, 48)
+    RF_LD(greg[0], gp, 0) RF_LD(greg[1], gp, 16) RF_LD(greg[2], gp, 32) RF_LD(greg[3], gp, 48)
+#undef RF_LD
   };
-  auto store_tiles = [&]() {
-    float gf[8];
+  // wait until at most PENDING younger vector-memory operations are in flight
+#define RF_WAIT_X(PENDING)                                                                   \
+  asm volatile("s_waitcnt vmcnt(%8)"                                                         \
+               : "+v"(xreg[0]), "+v"(xreg[1]), "+v"(xreg[2]), "+v"(xreg[3]), "+v"(greg[0]),  \
+                 "+v"(greg[1]), "+v"(greg[2]), "+v"(greg[3])                                 \
+               : "n"(PENDING));
+  // x*g -> bf16 -> LDS stage BUF (raw LDS writes: the compiler would order ordinary
+  // ones behind the direct-to-LDS loads still in flight)
+  uint32_t xdst_addr[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { gf[2 * j] = bf16_lo(greg[j]); gf[2 * j + 1] = bf16_hi(greg[j]); }
+  for (int c = 0; c < 4; ++c) xdst_addr[c] = lds_base + xdst[c];
+  auto store_x = [&](auto buf_tag, auto pending_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    constexpr int PENDING = decltype(pending_tag)::value;
+    RF_WAIT_X(PENDING)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int c = 0; c < 4; ++c) {
       u32x4 r;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float a = bf16_lo(xreg[e][j]), bq = bf16_hi(xreg[e][j]);
-        ss[e] = fmaf(a, a, ss[e]);   // stage 1 side accumulator
-        ss[e] = fmaf(bq, bq, ss[e]);
-        r[j] = pack_bf16(a * gf[2 * j], bq * gf[2 * j + 1]);
+        const float a = bf16_lo(xreg[c][j]), b = bf16_hi(xreg[c][j]);
+        ss = fmaf(a, a, ss);  // stage 1 side accumulator
+        ss = fmaf(b, b, ss);
+        r[j] = pack_bf16(a * bf16_lo(greg[c][j]), b * bf16_hi(greg[c][j]));
       }
-      *reinterpret_cast<u32x4*>(xs + tile_off(xrow + 32 * e, xpiece)) = r;
-    }
-    // W: 4 k-rows x 8 n-columns -> 8 rows of w^T, 4 k-values (8 bytes) each
-#pragma unroll
-    for (int tp = 0; tp < 4; ++tp) {
-      u32x2 lo2, hi2;
-      lo2[0] = pair_lo(wreg[0][tp], wreg[1][tp]);
-      lo2[1] = pair_lo(wreg[2][tp], wreg[3][tp]);
-      hi2[0] = pair_hi(wreg[0][tp], wreg[1][tp]);
-      hi2[1] = pair_hi(wreg[2][tp], wreg[3][tp]);
-      const int nrow = 8 * wpiece + 2 * tp;
-      *reinterpret_cast<u32x2*>(wts + tile_off(nrow, wkg >> 1) + 8 * (wkg & 1)) = lo2;
-      *reinterpret_cast<u32x2*>(wts + tile_off(nrow + 1, wkg >> 1) + 8 * (wkg & 1)) = hi2;
+      const uint32_t addr = xdst_addr[c] + BUF * kStageB;  // (stage offset exceeds the 16-bit field)
+      asm volatile("ds_write_b128 %0, %1" : : "v"(addr), "v"(r) : "memory");
     }
   };
 
-  load_tiles(0);
-  for (int k0 = 0; k0 < K; k0 += kBKK) {
-    __syncthreads();
-    store_tiles();
-    __syncthreads();
-    if (k0 + kBKK < K) load_tiles(k0 + kBKK);
-#pragma unroll
-    for (int kk = 0; kk < kBKK / 16; ++kk) {
-      u32x4 af[2], bfr[2];
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-        af[ni] = *reinterpret_cast<const u32x4*>(wts + tile_off(64 * wn + 32 * ni + i32, 2 * kk + hh));
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        bfr[mi] = *reinterpret_cast<const u32x4*>(xs + tile_off(64 * wm + 32 * mi + i32, 2 * kk + hh));
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, af[ni]), __builtin_bit_cast(bf16x8, bfr[mi]), acc[ni][mi],
-              0, 0, 0);
-    }
+  // One K step out of LDS stage BUF.  Fragment reads are raw instructions with
+  // hand-placed waits (the compiler would otherwise wait for the in-flight
+  // direct-to-LDS loads of the next stage before every transpose read).
+  auto compute = [&](auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    u32x2 af[2][2][2];  // [stage][ni][w2]
+    u32x4 bfr[2][4];    // [stage][mi]
+#define RF_ISSUE(STAGE, KK)                                                                  \
+  _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) {                                         \
+    _Pragma("unroll") for (int w2 = 0; w2 < 2; ++w2) asm volatile(                           \
+        "ds_read_b64_tr_b16 %0, %1 offset:%2"                                                \
+        : "=v"(af[STAGE][ni][w2])                                                            \
+        : "v"(waddr[BUF][ni][w2]), "n"((KK) * 16 * 512));                                    \
+  }                                                                                          \
+  _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) asm volatile(                             \
+      "ds_read_b128 %0, %1 offset:%2"                                                        \
+      : "=v"(bfr[STAGE][mi])                                                                 \
+      : "v"(xaddr[BUF][KK]), "n"(mi * 32 * 128));
+#define RF_WAIT(STAGE, PENDING)                                                              \
+  asm volatile("s_waitcnt lgkmcnt(%8)"                                                       \
+               : "+v"(af[STAGE][0][0]), "+v"(af[STAGE][0][1]), "+v"(af[STAGE][1][0]),        \
+                 "+v"(af[STAGE][1][1]), "+v"(bfr[STAGE][0]), "+v"(bfr[STAGE][1]),            \
+                 "+v"(bfr[STAGE][2]), "+v"(bfr[STAGE][3])                                    \
+               : "n"(PENDING));
+#define RF_MFMA(STAGE)                                                                       \
+  _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) {                                         \
+    u32x4 a;                                                                                 \
+    a[0] = af[STAGE][ni][0][0]; a[1] = af[STAGE][ni][0][1];                                  \
+    a[2] = af[STAGE][ni][1][0]; a[3] = af[STAGE][ni][1][1];                                  \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) acc[ni][mi] =                           \
+        __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),               \
+                                                __builtin_bit_cast(bf16x8, bfr[STAGE][mi]),  \
+                                                acc[ni][mi], 0, 0, 0);                       \
   }
+    RF_ISSUE(0, 0)
+    RF_ISSUE(1, 1)
+    RF_WAIT(0, 8)
+    RF_MFMA(0)
+    RF_ISSUE(0, 2)
+    RF_WAIT(1, 8)
+    RF_MFMA(1)
+    RF_ISSUE(1, 3)
+    RF_WAIT(0, 8)
+    RF_MFMA(0)
+    RF_WAIT(1, 0)
+    RF_MFMA(1)
+#undef RF_ISSUE
+#undef RF_WAIT
+#undef RF_MFMA
+  };
 
-  // stage 1 result: the 8 lanes that share an X row add their partial sums
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float s = ss[e];
-    s += dpp_f32<kDppQuadXor1>(s);
-    s += dpp_f32<kDppQuadXor2>(s);
-    s += dpp_f32<kDppRowHalfMirror>(s);
-    if (xpiece == 0) s_rstd[xrow + 32 * e] = 1.0f / sqrtf(s * inv_k + eps);
+  // K step k0 computes out of stage BUF while tile k0+64 is converted into stage
+  // BUF^1 (its X registers were loaded one step earlier) and tile k0+128 is fetched.
+  // The two wavefronts that share a SIMD (w and w+4) take the two phases in opposite
+  // order, so one's MFMA phase overlaps the other's VALU phase.
+  // Vector-memory issue order per step: 4 W loads (top), 8 X/g loads (end); loads
+  // retire in order, which fixes the counts in the waits below.
+  using std::integral_constant;
+  auto k_step = [&](int k0, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    using other = integral_constant<int, BUF ^ 1>;
+    const bool more = k0 + kBKK < K;
+    // this stage's W loads have landed (the 8 younger X/g loads may still fly) and our
+    // LDS writes are done
+    if (more)
+      asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // the whole stage is in LDS; the other stage is free
+    if (more) issue_w(k0 + kBKK, BUF ^ 1);
+    const bool more2 = k0 + 2 * kBKK < K;
+    if (wave < 4) {
+      compute(buf_tag);
+      if (more) store_x(other{}, integral_constant<int, 4>{});
+      if (more2) load_x(k0 + 2 * kBKK);
+    } else {
+      if (more) store_x(other{}, integral_constant<int, 4>{});
+      if (more2) load_x(k0 + 2 * kBKK);  // a whole step ahead of its use
+      compute(buf_tag);
+    }
+  };
+
+  issue_w(0, 0);
+  load_x(0);
+  store_x(integral_constant<int, 0>{}, integral_constant<int, 0>{});
+  if (kBKK < K) load_x(kBKK);
+  for (int k0 = 0; k0 < K; k0 += 2 * kBKK) {
+    k_step(k0, integral_constant<int, 0>{});
+    if (k0 + kBKK < K) k_step(k0 + kBKK, integral_constant<int, 1>{});
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef RF_WAIT_X
+
+  // stage 1 result: the two lanes that share an X row add their partial sums
+  ss += dpp_f32<kDppQuadXor1>(ss);
+  if (xhalf == 0) s_rstd[xrow] = 1.0f / sqrtf(ss * inv_k + eps);
   __syncthreads();
 
   // epilogue: y = acc * H(ss)
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
-    const int mloc = 64 * wm + 32 * mi + i32;
+  for (int mi = 0; mi < 4; ++mi) {
+    const int mloc = 128 * wm + 32 * mi + i32;
     const int m = m0 + mloc;
     const float rs = s_rstd[mloc];
     if (m >= M) continue;
@@ -181,9 +306,10 @@ hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w,
   const int n_ntiles = (N + kBN - 1) / kBN;
   const int64_t grid = (int64_t)n_mtiles * n_ntiles;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
+  if (ldw >= (1 << 24)) return hipErrorInvalidValue;  // 32-bit byte offsets inside a 64-row tile
   hipLaunchKernelGGL(rmsnorm_gemm_bf16_kernel, dim3((unsigned)grid), dim3(kGThreads), 0, s,
                      (const bf16_t*)x, (const bf16_t*)g, (const bf16_t*)w, (bf16_t*)y, M, K, N, ldx,
-                     ldw, ldy, 1.0f / (float)K, eps, n_mtiles);
+                     ldw, ldy, 1.0f / (float)K, eps, n_mtiles, n_ntiles);
   return hipGetLastError();
 }
 

@@ -249,15 +249,12 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
     __builtin_amdgcn_s_barrier();  // the whole stage is in LDS; the other stage is free
     if (more) issue_w(k0 + kBKK, BUF ^ 1);
     const bool more2 = k0 + 2 * kBKK < K;
-    if (wave < 4) {
-      compute(buf_tag);
-      if (more) store_x(other{}, integral_constant<int, 4>{});
-      if (more2) load_x(k0 + 2 * kBKK);
-    } else {
-      if (more) store_x(other{}, integral_constant<int, 4>{});
-      if (more2) load_x(k0 + 2 * kBKK);  // a whole step ahead of its use
-      compute(buf_tag);
-    }
+    // (one program point for the asynchronous X loads: their registers must not be
+    // copied by the compiler while the loads are in flight)
+    if (wave < 4) compute(buf_tag);
+    if (more) store_x(other{}, integral_constant<int, 4>{});
+    if (more2) load_x(k0 + 2 * kBKK);  // a whole step ahead of its use
+    if (wave >= 4) compute(buf_tag);
   };
 
   issue_w(0, 0);

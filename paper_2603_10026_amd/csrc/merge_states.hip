@@ -11,7 +11,9 @@ namespace rf {
 
 constexpr int kMergeThreads = 256;
 
-template <bool OUT_BF16>
+constexpr int kPre = 8;  // acc loads a thread can issue before it knows the weights
+
+template <bool OUT_BF16, bool PREFETCHED>
 __global__ __launch_bounds__(kMergeThreads) void merge_states_kernel(
     const float* __restrict__ part_m, const float* __restrict__ part_l,
     const float* __restrict__ part_acc, void* __restrict__ o, int Hq, int Lq, int S, int d,
@@ -28,6 +30,22 @@ __global__ __launch_bounds__(kMergeThreads) void merge_states_kernel(
   const float* pl = part_l + row * S;
   const float* pa = part_acc + row * (int64_t)S * d;
   const int tid = threadIdx.x;
+
+  // The acc loads do not depend on the weights: when a thread has at most kPre
+  // chunks, issue them all now so that the whole kernel pays one memory latency.
+  f32x4 pre[kPre];
+  if (PREFETCHED) {
+    const int G0 = kMergeThreads / ncol_p2;
+    const int c0 = tid % ncol_p2, sg0 = tid / ncol_p2;
+    if (c0 < d / 4) {
+#pragma unroll
+      for (int i = 0; i < kPre; ++i) {
+        const int s = sg0 + i * G0;
+        pre[i] = (s < S) ? *reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c0)
+                         : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  }
 
   // m = max over chunks
   float m = -INFINITY;
@@ -56,12 +74,25 @@ __global__ __launch_bounds__(kMergeThreads) void merge_states_kernel(
   const int sg = tid / ncol_p2;
   f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
   if (c < ncol) {
-    for (int s = sg; s < S; s += G) {
-      const float mc = pm[s];
-      if (mc == -INFINITY) continue;
-      const float w = fast_exp2((mc - m_use) * kLog2e);
-      const f32x4 a = *reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c);
-      sum += a * w;
+    if (PREFETCHED) {
+      // (the kPre loads of this thread were issued at kernel entry)
+#pragma unroll
+      for (int i = 0; i < kPre; ++i) {
+        const int s = sg + i * G;
+        if (s < S) {
+          const float mc = pm[s];
+          const float w = (mc == -INFINITY) ? 0.f : fast_exp2((mc - m_use) * kLog2e);
+          sum += ((mc == -INFINITY) ? f32x4{0.f, 0.f, 0.f, 0.f} : pre[i]) * w;
+        }
+      }
+    } else {
+      for (int s = sg; s < S; s += G) {
+        const float mc = pm[s];
+        if (mc == -INFINITY) continue;
+        const float w = fast_exp2((mc - m_use) * kLog2e);
+        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c);
+        sum += a * w;
+      }
     }
   }
   s_part[tid] = sum;
@@ -90,12 +121,13 @@ hipError_t launch_merge_states(const float* part_m, const float* part_l, const f
   int p2 = 1;
   while (p2 < ncol) p2 <<= 1;
   if (p2 > kMergeThreads) return hipErrorInvalidValue;
-  if (o_is_bf16)
-    hipLaunchKernelGGL((merge_states_kernel<true>), dim3((unsigned)rows), dim3(kMergeThreads), 0, s,
-                       part_m, part_l, part_acc, o, Hq, Lq, S, d, p2, so);
-  else
-    hipLaunchKernelGGL((merge_states_kernel<false>), dim3((unsigned)rows), dim3(kMergeThreads), 0,
-                       s, part_m, part_l, part_acc, o, Hq, Lq, S, d, p2, so);
+  const bool pre = S <= kPre * (kMergeThreads / p2);
+#define RF_MERGE_LAUNCH(B16, PRE)                                                                  \
+  hipLaunchKernelGGL((merge_states_kernel<B16, PRE>), dim3((unsigned)rows), dim3(kMergeThreads), 0, \
+                     s, part_m, part_l, part_acc, o, Hq, Lq, S, d, p2, so)
+  if (o_is_bf16) { if (pre) RF_MERGE_LAUNCH(true, true); else RF_MERGE_LAUNCH(true, false); }
+  else { if (pre) RF_MERGE_LAUNCH(false, true); else RF_MERGE_LAUNCH(false, false); }
+#undef RF_MERGE_LAUNCH
   return hipGetLastError();
 }
 

@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--only", type=str, default="", help="comma list of w0..w4 (profiling aid); default all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one plain 256 MiB -> 256 MiB copy kernel before the warmup "
+                         "(reference dispatch for scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -127,6 +130,15 @@ def main():
             if events is not None:
                 events[j][1].record()
 
+    if args.calib_copy:
+        # plain copy kernel of known size: reads 256 MiB, writes 256 MiB
+        src = torch.ones(1 << 26, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         run_step(i)
     torch.cuda.synchronize()
@@ -171,6 +183,16 @@ def main():
     work["w4_rmsnorm_gemm"] = dict(bound="mfma", flops=2.0 * c["M"] * c["K"] * c["N"],
                                    bytes=2.0 * (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] + c["K"]))
 
+    # HBM-side traffic per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+    # scaled by a plain copy kernel (recorded in profiles/; None when no record exists)
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "bench_all_workloads_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 4 and f[0] == "TRAFFIC":
+                traffic[f[1]] = float(f[2]) + float(f[3])
+
     workloads = {}
     rooflines = []
     for label, _ in launches:
@@ -181,12 +203,12 @@ def main():
             ach = wk["bytes"] / sec / 1e9
             entry.update(GBps=round(ach, 1), frac=round(ach / PEAK_HBM_GBS, 4), algorithmic_bytes=wk["bytes"])
             rooflines.append(dict(kernel=label, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                                  frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, us=round(d["avg"], 2)))
+                                  frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic.get(label), us=round(d["avg"], 2)))
         elif wk["bound"] == "mfma":
             ach = wk["flops"] / sec / 1e12
             entry.update(TFLOPs=round(ach, 1), frac=round(ach / PEAK_BF16_TFLOPS, 4), algorithmic_flops=wk["flops"])
             rooflines.append(dict(kernel=label, bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS,
-                                  unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                                  unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=traffic.get(label),
                                   us=round(d["avg"], 2)))
         else:
             entry.update(TFLOPs=round(wk["flops"] / sec / 1e12, 3), note="launch-latency bound; time is the figure of merit")
@@ -211,16 +233,17 @@ def main():
             cores = os.cpu_count() or 1
         c = W[2]
         s2 = state["w2"]
-        nh = 16                                  # heads of batch 0: a bounded sample of the same workload
-        qh, kh, vh = (I.to_numpy(t[:1, :nh]) for t in (s2["q"], s2["k"], s2["v"]))
+        nb, nh = 2, c["Hq"]                      # two of the four batches: a bounded sample of the same workload
+        qh, kh, vh = (I.to_numpy(t[:nb]) for t in (s2["q"], s2["k"], s2["v"]))
         tc0 = time.perf_counter()
         ref = O.attention(qh, kh, vh, s2["scale"], False)
         tc1 = time.perf_counter()
-        fl = 4.0 * nh * c["Lq"] * c["Lk"] * c["d"]
-        got = I.to_numpy(s2["o"][:1, :nh])
+        fl = 4.0 * nb * nh * c["Lq"] * c["Lk"] * c["d"]
+        got = I.to_numpy(s2["o"][:nb])
         err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
         cpu = dict(value=round(fl / (tc1 - tc0) / 1e12, 5), unit="TFLOP/s", cores=int(cores), kind="oracle",
-                   sample=f"{nh} of {c['B'] * c['Hq']} heads of the non-causal prefill workload, fp64 numpy, {tc1 - tc0:.1f} s",
+                   sample=f"{nb * nh} of {c['B'] * c['Hq']} (batch, head) pairs of the non-causal prefill workload, "
+                          f"fp64 numpy oracle, {tc1 - tc0:.1f} s wall",
                    gpu_vs_oracle_max_err_over_max_ref=err)
 
     primary = workloads.get("w2_attention_prefill")

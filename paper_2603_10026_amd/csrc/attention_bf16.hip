@@ -224,79 +224,30 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     const unsigned char* kt_lds = lds + BUF * 2 * TILEB;
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
-    // The K fragments of contraction steps 2i, 2i+1 are fetched while the MFMAs of
-    // steps 2i-2, 2i-1 run (two-stage register pipeline).
+    // All K fragments are requested before the first MFMA: LDS latency is paid once per
+    // tile, not once per contraction step.
     f32x16 s[2];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[rt][r] = 0.f;
-    u32x4 kf[2][4];
-    auto load_kf = [&](int stage, int step) {
+    u32x4 kf[KS][2];
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-          kf[stage][2 * c + rt] =
-              *reinterpret_cast<const u32x4*>(kt_lds + koff[2 * step + c] + rt * 32 * ROWB);
-    };
-    load_kf(0, 0);
-#pragma unroll
-    for (int step = 0; step < KS / 2; ++step) {
-      if (step + 1 < KS / 2) load_kf((step + 1) & 1, step + 1);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-          s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, kf[step & 1][2 * c + rt]),
-              __builtin_bit_cast(bf16x8, qf[2 * step + c]), s[rt], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // s[rt][r] = raw score(key key0 + 32rt + 8(r/4) + 4hh + r%4, query my_q)
-    if (key0 + kBK - 1 > wave_min_last) {  // uniform: tile crosses the mask boundary
+    for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
+        kf[kk][rt] = *reinterpret_cast<const u32x4*>(kt_lds + koff[kk] + rt * 32 * ROWB);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + 32 * rt + 8 * (r >> 2) + 4 * hh + (r & 3);
-          s[rt][r] = (key <= my_last) ? s[rt][r] : -INFINITY;
-        }
-    }
-    // ---- stage 1: running max (reference point advanced lazily) ----
-    float tmax = -INFINITY;
+    for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[rt][r]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float tmax2 = tmax * scale_log2e;  // log2 units; scale > 0 keeps the order
-    if (__builtin_amdgcn_ballot_w64(tmax2 > m_ref + kTau) != 0) {
-      const float m_new = fmaxf(m_ref, tmax2);
-      const float corr = (m_new == -INFINITY) ? 1.0f : fast_exp2(m_ref - m_new);
-      m_ref = m_new;
-      l *= corr;
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] *= corr;
-    }
-    // ---- stage 2: running sum of exponentials; P^T packed to bf16 B operands ----
-    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-    float psum = 0.f;
-    u32x4 pb[4];
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-      for (int r2 = 0; r2 < 8; ++r2) {
-        const float p0 = fast_exp2(fmaf(s[rt][2 * r2], scale_log2e, neg_m));
-        const float p1 = fast_exp2(fmaf(s[rt][2 * r2 + 1], scale_log2e, neg_m));
-        psum += p0 + p1;
-        pb[2 * rt + (r2 >> 2)][r2 & 3] = pack_bf16(p0, p1);
-      }
-    l += psum;
-    // ---- stage 3: acc += V^T P^T ----
+      for (int rt = 0; rt < 2; ++rt)
+        s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk][rt]),
+                                                        __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
+                                                        0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- V^T fragments of the first two contraction steps: requested now, they arrive
+    //      while the softmax below runs on the vector ALU ----
     // The transpose reads are issued as raw instructions and waited for by hand:
     // going through the compiler's intrinsic would make it wait for the
     // direct-to-LDS loads of the NEXT tile before every read of this one.
@@ -330,9 +281,57 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                     \
         __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pb[U]), acc[t], 0, 0, 0); \
   }
-    constexpr int NV = 2 * DT;  // transpose reads per contraction step
     RF_ISSUE_V(0, 0)
     RF_ISSUE_V(1, 1)
+    // s[rt][r] = raw score(key key0 + 32rt + 8(r/4) + 4hh + r%4, query my_q)
+    if (key0 + kBK - 1 > wave_min_last) {  // uniform: tile crosses the mask boundary
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + 32 * rt + 8 * (r >> 2) + 4 * hh + (r & 3);
+          s[rt][r] = (key <= my_last) ? s[rt][r] : -INFINITY;
+        }
+    }
+    // ---- stage 1: running max (reference point advanced lazily) ----
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[rt][r]);
+    {
+      // lane l <-> lane l^32 through a VALU lane swap (no LDS round trip)
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax),
+                                                       false, false);
+      tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    const float tmax2 = tmax * scale_log2e;  // log2 units; scale > 0 keeps the order
+    if (__builtin_amdgcn_ballot_w64(tmax2 > m_ref + kTau) != 0) {
+      const float m_new = fmaxf(m_ref, tmax2);
+      const float corr = (m_new == -INFINITY) ? 1.0f : fast_exp2(m_ref - m_new);
+      m_ref = m_new;
+      l *= corr;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] *= corr;
+    }
+    // ---- stage 2: running sum of exponentials; P^T packed to bf16 B operands ----
+    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
+    float psum = 0.f;
+    u32x4 pb[4];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r2 = 0; r2 < 8; ++r2) {
+        const float p0 = fast_exp2(fmaf(s[rt][2 * r2], scale_log2e, neg_m));
+        const float p1 = fast_exp2(fmaf(s[rt][2 * r2 + 1], scale_log2e, neg_m));
+        psum += p0 + p1;
+        pb[2 * rt + (r2 >> 2)][r2 & 3] = pack_bf16(p0, p1);
+      }
+    l += psum;
+    // ---- stage 3: acc += V^T P^T ----
+    constexpr int NV = 2 * DT;  // transpose reads per contraction step
     RF_WAIT_V(0, NV)
     RF_PV_STEP(0, 0)
     RF_ISSUE_V(0, 2)

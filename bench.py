@@ -222,6 +222,35 @@ def main():
 
     dominant = max(rooflines, key=lambda r: r["us"]) if rooflines else None
 
+    # -------------------------------------------- measured ceilings (context, not the peaks)
+    def timed(fn, n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(0)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(n):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / n
+
+    nbytes = 256 << 20
+    srcs = [torch.ones(nbytes // 4, dtype=torch.float32, device=dev) for _ in range(N_ROT)]
+    dsts = [torch.empty_like(t) for t in srcs]
+    t_copy = timed(lambda i: rf.rf_diag_copy(srcs[i % N_ROT], dsts[i % N_ROT]), 12)
+    del srcs, dsts
+    sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    fl = 512 * 4 * 300 * 32 * 32768.0
+    t_rand = timed(lambda i: rf.rf_diag_mfma(sink, 512, 300, True), 5)
+    t_const = timed(lambda i: rf.rf_diag_mfma(sink, 512, 300, False), 5)
+    ceilings = dict(hbm_copy_GBps=round(2 * nbytes / t_copy / 1e9, 1),
+                    mfma_bf16_random_operands_TFLOPs=round(fl / t_rand / 1e12, 1),
+                    mfma_bf16_constant_operands_TFLOPs=round(fl / t_const / 1e12, 1),
+                    note="plain 256 MiB copy kernel; MFMA-only 32x32x16 bf16 loop, 512 workgroups x 4 wavefronts")
+    for r in rooflines:
+        ceil = ceilings["hbm_copy_GBps"] if r["bound"] == "hbm" else ceilings["mfma_bf16_random_operands_TFLOPs"]
+        r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
+
     # ------------------------------------------------------------ cpu baseline
     cpu = None
     if not args.no_cpu_baseline and "w2" in only:
@@ -267,6 +296,7 @@ def main():
         "workloads": workloads,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]} if dominant else None,
         "rooflines": rooflines,
+        "ceilings": ceilings,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -151,6 +151,22 @@ RF_API rf_status rf_merge_states(const rf_tensor* part_m, const rf_tensor* part_
 RF_API rf_status rf_rmsnorm_gemm(const rf_tensor* x, const rf_tensor* g, const rf_tensor* w,
                           rf_tensor* y, float eps, rf_stream stream);
 
+/*
+ * Measurement aids, not part of the cascaded-reduction path.  They provide the two
+ * measured ceilings that roofline fractions are reported next to (a plain copy kernel for
+ * HBM, an MFMA-only loop for the matrix pipe) and the reference dispatch that scales the
+ * FETCH_SIZE / WRITE_SIZE hardware counters.
+ *   rf_diag_copy : dst[0..bytes) = src[0..bytes); device pointers, 16-byte aligned,
+ *                  bytes a multiple of 16, buffers must not overlap.
+ *   rf_diag_mfma : `workgroups` workgroups of 4 wavefronts each issue iters*32 dense bf16
+ *                  32x32x16 MFMAs (32768 flop each) on constant (random_operands == 0) or
+ *                  pseudo-random operands; `sink` is a device buffer of workgroups*256 floats
+ *                  that receives the accumulator sums.
+ */
+RF_API rf_status rf_diag_copy(const void* src, void* dst, int64_t bytes, rf_stream stream);
+RF_API rf_status rf_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
+                              rf_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

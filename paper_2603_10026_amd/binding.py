@@ -29,6 +29,8 @@ ENTRY_POINTS = (
     "rf_cascade_attention_splitk",
     "rf_merge_states",
     "rf_rmsnorm_gemm",
+    "rf_diag_copy",
+    "rf_diag_mfma",
 )
 
 
@@ -81,6 +83,10 @@ def load_library():
     lib.rf_merge_states.argtypes = [P, P, P, P, ctypes.c_void_p]
     lib.rf_rmsnorm_gemm.restype = ctypes.c_int
     lib.rf_rmsnorm_gemm.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_void_p]
+    lib.rf_diag_copy.restype = ctypes.c_int
+    lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    lib.rf_diag_mfma.restype = ctypes.c_int
+    lib.rf_diag_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -192,3 +198,22 @@ def rf_rmsnorm_gemm(x, g, w, eps=1e-6, y=None, stream=None):
     _check(lib.rf_rmsnorm_gemm(ctypes.byref(dx), ctypes.byref(dg), ctypes.byref(dw),
                                ctypes.byref(dy), float(eps), _stream(stream)), "rf_rmsnorm_gemm")
     return y
+
+
+def rf_diag_copy(src, dst, stream=None):
+    """Plain copy kernel of known size (measurement aid): dst <- src, same byte size."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib.rf_diag_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()),
+                            nbytes, _stream(stream)), "rf_diag_copy")
+    return dst
+
+
+def rf_diag_mfma(sink, workgroups, iters, random_operands, stream=None):
+    """MFMA-only loop (measurement aid); returns the flop count of the launch."""
+    lib = load_library()
+    assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
+    _check(lib.rf_diag_mfma(ctypes.c_void_p(sink.data_ptr()), int(workgroups), int(iters),
+                            int(bool(random_operands)), _stream(stream)), "rf_diag_mfma")
+    return workgroups * 4 * iters * 32 * 32768.0

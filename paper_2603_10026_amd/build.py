@@ -22,6 +22,7 @@ SOURCES = [
     "attention_splitk.hip",
     "merge_states.hip",
     "rmsnorm_gemm.hip",
+    "diag.hip",
 ]
 
 HIPCC_FLAGS = [

@@ -287,4 +287,24 @@ rf_status rf_rmsnorm_gemm(const rf_tensor* x, const rf_tensor* g, const rf_tenso
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 
+rf_status rf_diag_copy(const void* src, void* dst, int64_t bytes, rf_stream stream) {
+  if (bytes < 0) return RF_ERR_INVALID_ARG;
+  if (bytes == 0) return RF_OK;
+  if (src == nullptr || dst == nullptr) return RF_ERR_INVALID_ARG;
+  if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(dst) % 16 != 0)
+    return RF_ERR_ALIGNMENT;
+  hipError_t e = rf::launch_diag_copy(src, dst, bytes, (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
+rf_status rf_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
+                       rf_stream stream) {
+  if (sink == nullptr || workgroups < 1 || iters < 0 || workgroups > (1 << 20))
+    return RF_ERR_INVALID_ARG;
+  hipError_t e = rf::launch_diag_mfma(sink, workgroups, iters, random_operands != 0,
+                                      (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -47,4 +47,11 @@ hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w,
                                     int K, int N, int64_t ldx, int64_t ldw, int64_t ldy,
                                     float eps, hipStream_t s);
 
+// Measurement aids: a plain copy of `bytes` (multiple of 16) and an MFMA-only loop
+// (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
+// workgroups * 256 floats).
+hipError_t launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
+hipError_t launch_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
+                            hipStream_t s);
+
 }  // namespace rf

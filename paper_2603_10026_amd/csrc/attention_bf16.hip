@@ -87,14 +87,29 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
   const int hh = lane >> 5;
 
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
-  // them so that an XCD receives consecutive ids: the query tiles of one head then
-  // share that head's K/V in one L2, and every XCD gets the same mix of heavy and
-  // light tiles under a causal mask.
-  int vid = blockIdx.x;
-  if ((gridDim.x & 7) == 0) vid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-  // heavy (late) query tiles first: under a causal mask they have the most keys
-  const int qt = n_qtiles - 1 - (vid % n_qtiles);
-  const int bh = vid / n_qtiles;
+  // them so that an XCD owns a contiguous range of heads: the query tiles of one head
+  // then share that head's K/V in one L2.
+  //  - no mask: head-major inside the XCD, so all query tiles of a head run together and
+  //    each K/V tile is fetched into the L2 once;
+  //  - causal mask: query-tile-major, heaviest first.  The late query tiles see the most
+  //    keys; starting all of them before any light tile keeps the tail of the launch short.
+  int qt, bh;
+  const int n_bh = gridDim.x / n_qtiles;
+  if ((n_bh & 7) == 0) {
+    const int hx = n_bh >> 3;            // heads per XCD
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;       // arrival order inside the XCD
+    if (causal) {
+      qt = n_qtiles - 1 - j / hx;
+      bh = xcd * hx + j % hx;
+    } else {
+      qt = j % n_qtiles;
+      bh = xcd * hx + j / n_qtiles;
+    }
+  } else {
+    qt = n_qtiles - 1 - (int)(blockIdx.x / n_bh);
+    bh = blockIdx.x % n_bh;
+  }
   const int h = bh % Hq;
   const int b = bh / Hq;
   const int hk = h / (Hq / Hkv);

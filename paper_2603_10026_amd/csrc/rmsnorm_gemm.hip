@@ -59,13 +59,24 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
   const int wn = wave & 3;   // 64-column block of the N tile
   const int wm = wave >> 2;  // 128-row block of the M tile
 
-  // XCD-aware numbering: workgroups are dealt round-robin to 8 XCDs; give each XCD
-  // a run of consecutive tiles so that its L2 sees a few X row strips and W column
-  // strips many times instead of all of them once.
-  int vid = blockIdx.x;
-  if ((gridDim.x & 7) == 0) vid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-  const int mt = vid / n_ntiles;
-  const int nt = vid % n_ntiles;
+  // XCD-aware numbering: workgroups are dealt round-robin to the 8 XCDs, each with its
+  // own L2.
+  int mt, nt;
+  {
+    const int n_mtiles = gridDim.x / n_ntiles;
+    if ((n_mtiles & 3) == 0 && (n_ntiles & 1) == 0) {
+      // XCD x owns the block of (n_mtiles/4) x (n_ntiles/2) output tiles at block row x/2,
+      // block column x%2: the squarest split into 8, so its L2 fetches the fewest
+      // X row panels plus W column panels.
+      const int bm = n_mtiles >> 2, bn = n_ntiles >> 1;
+      const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+      mt = (xcd >> 1) * bm + jj / bn;
+      nt = (xcd & 1) * bn + jj % bn;
+    } else {
+      mt = blockIdx.x / n_ntiles;
+      nt = blockIdx.x % n_ntiles;
+    }
+  }
   const int m0 = mt * kBM, n0 = nt * kBN;
 
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;

@@ -12,8 +12,8 @@ definition contains one.
 Two groups of functions:
 
 * ``safe_softmax``, ``attention``, ``attention_partial_states``,
-  ``merge_states``, ``rmsnorm_gemm``: the definitions the GPU results are
-  compared against.
+  ``merge_states``, ``rmsnorm_gemm``, ``variance``, ``moe_routing``: the
+  definitions the GPU results are compared against.
 * ``*_incremental`` and ``fused_*``: the paper's fused / incremental forms
   (Section 3.2 Eq. (6), (8), (11); Section 3.3 Eq. (15)-(16); Appendix A.2) written out
   step by step in the paper's order.  They exist so that the tests can check
@@ -36,7 +36,15 @@ Readings of the paper taken here (each is also listed in the design notes):
     identity of the combine operator);
   * RMSNorm + linear: H(ss) = (ss/K + eps)^(-1/2), eps added to the mean of
     squares; the clamp printed in the "Sum + Sum" example is garbled and is not
-    used.
+    used;
+  * variance (Appendix, non-ML workloads) is the population variance (both
+    reductions divide by L0).  Its second map (x - m)^2 is not of the form
+    G(x) (x) H(m); the fused forms expand the square into decomposable terms,
+    which gives the pairwise update of (count, mean, M2);
+  * MoE routing (Appendix A.2): TopK acts on the raw scores (softmax keeps
+    their order) and the final "s / t" is read as exp(s - m) / t, the softmax
+    probability of each selected expert.  Equal scores are ordered by expert
+    index, lowest first, and the k outputs are in descending order of score.
 """
 from __future__ import annotations
 
@@ -378,3 +386,123 @@ def F_weighted(p, vj, m, t):
 def F_rms(xk, gk, wk, ss, K, eps):
     """Mapping function of reduction 2 of RMSNorm + linear."""
     return xk * gk * wk / np.sqrt(ss / K + eps)
+
+
+# --------------------------------------------------------------------------
+# O6. variance  (Appendix, evaluation on non-ML workloads)
+# --------------------------------------------------------------------------
+def variance(x):
+    """Row-wise mean and population variance as two dependent reductions.
+
+    reduction 1: m = (1/L) sum_l x[l];  reduction 2: var = (1/L) sum_l (x[l]-m)^2.
+    Returns (m, var), each of shape x.shape[:-1].
+    """
+    x = np.asarray(x, dtype=F64)
+    L = x.shape[-1]
+    m = np.sum(x, axis=-1) / L                                # reduction 1
+    d = x - m[..., None]
+    var = np.sum(d * d, axis=-1) / L                          # reduction 2
+    return m, var
+
+
+def variance_segment_state(x):
+    """Level-1 fused state of one segment: (n, mean, M2) with
+    M2 = sum_l (x[l] - mean)^2 over the segment; the empty segment is (0, 0, 0)."""
+    x = np.asarray(x, dtype=F64)
+    n = x.shape[0]
+    if n == 0:
+        return 0, 0.0, 0.0
+    mean = float(np.sum(x)) / n
+    return n, mean, float(np.sum((x - mean) ** 2))
+
+
+def variance_fused_levelk(states):
+    """Level-k fused form over segment states: the mean of the union is the
+    count-weighted mean; every segment's M2 is moved to the new mean with
+    sum (x-c)^2 = sum (x-mean_s)^2 + n_s (mean_s - c)^2 (the cross term of the
+    expanded square vanishes)."""
+    n = sum(s[0] for s in states)
+    if n == 0:
+        return 0, 0.0, 0.0
+    mean = sum(s[0] * s[1] for s in states) / n
+    m2 = sum(s[2] + s[0] * (s[1] - mean) ** 2 for s in states)
+    return n, mean, m2
+
+
+def variance_incremental(states):
+    """Level-k incremental form: fold segment states one by one.  A single
+    element is the state (1, x, 0), which gives the level-1 incremental form."""
+    n, mean, m2 = 0, 0.0, 0.0
+    for (nc, meanc, m2c) in states:
+        if nc == 0:
+            continue
+        n_new = n + nc
+        delta = meanc - mean
+        mean_new = mean + delta * nc / n_new
+        m2 = m2 + m2c + delta * delta * n * nc / n_new
+        n, mean = n_new, mean_new
+    return n, mean, m2
+
+
+# --------------------------------------------------------------------------
+# O7. MoE routing: scores GEMM -> softmax -> top-k  (Appendix A.2, MoE routing)
+# --------------------------------------------------------------------------
+def topk_desc(values, k):
+    """Indices of the k largest entries of a 1-D array, largest first; equal
+    values in ascending index order."""
+    values = np.asarray(values, dtype=F64)
+    order = sorted(range(values.shape[0]), key=lambda j: (-values[j], j))
+    return np.asarray(order[:k], dtype=np.int64)
+
+
+def moe_routing(x, w, topk):
+    """Router of a mixture-of-experts layer, as separate reductions per token.
+
+    reduction 0: p[e] = sum_c x[c] w[c, e]          (the scores GEMM)
+    reduction 1: m = max_e p[e]
+    reduction 2: t = sum_e exp(p[e] - m)
+    reduction 3: s = TopK_e p[e]                    (k largest scores, with their experts)
+    output:      exp(s - m) / t                     (softmax probability of the selected experts)
+    x [S, hd]; w [hd, E].  Returns (prob [S, topk] float64, idx [S, topk] int64, p [S, E]).
+    """
+    x = np.asarray(x, dtype=F64)
+    w = np.asarray(w, dtype=F64)
+    p = x @ w                                                 # reduction 0
+    S, E = p.shape
+    prob = np.empty((S, topk), dtype=F64)
+    idx = np.empty((S, topk), dtype=np.int64)
+    for i in range(S):
+        m = np.max(p[i])                                      # reduction 1
+        t = np.sum(np.exp(p[i] - m))                          # reduction 2
+        sel = topk_desc(p[i], topk)                           # reduction 3
+        idx[i] = sel
+        prob[i] = np.exp(p[i, sel] - m) / t
+    return prob, idx, p
+
+
+def topk_merge(a, b, k):
+    """TopK of the union of two (value, index) lists: the combine step of the
+    mergeable TopK state (largest first, ties to the lower index)."""
+    both = sorted(list(a) + list(b), key=lambda vi: (-vi[0], vi[1]))
+    return both[:k]
+
+
+def moe_routing_incremental_row(p, topk, seg):
+    """Level-k incremental form for one token's scores p, fed in segments of
+    `seg` experts: every segment yields the level-1 fused state (m, t, TopK),
+    which is folded into the running state with
+    m' = max(m, m_s);  t' = t exp(m-m') + t_s exp(m_s-m');  s' = TopK(s, s_s)."""
+    p = np.asarray(p, dtype=F64)
+    m, t, s = NEG_INF, 0.0, []
+    for lo in range(0, p.shape[0], seg):
+        chunk = p[lo:lo + seg]
+        m_s = float(np.max(chunk))
+        t_s = float(np.sum(np.exp(chunk - m_s)))
+        s_s = [(float(chunk[j]), lo + int(j)) for j in topk_desc(chunk, min(topk, chunk.shape[0]))]
+        m_new = max(m, m_s)
+        t = t * _corr(m, m_new) + t_s * _corr(m_s, m_new)
+        s = topk_merge(s, s_s, topk)
+        m = m_new
+    prob = np.asarray([np.exp(v - m) / t for v, _ in s], dtype=F64)
+    idx = np.asarray([j for _, j in s], dtype=np.int64)
+    return prob, idx

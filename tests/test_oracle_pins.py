@@ -372,3 +372,150 @@ def test_decomposability_identity_and_g_h_factorisation():
     # a mapping that is NOT decomposable under (*): (x - d)^2
     F = lambda x, d: (x - d) ** 2
     assert F(1.0, 2.0) * F(3.0, 5.0) != pytest.approx(F(1.0, 5.0) * F(3.0, 2.0))
+
+
+# ----------------------------------------------------------------- variance
+def test_variance_closed_forms():
+    # constant row: mean c, variance 0 exactly
+    m, v = O.variance(np.full((2, 17), -3.5))
+    assert np.all(m == -3.5) and np.all(v == 0.0)
+    # 0, 1, ..., L-1: mean (L-1)/2, population variance (L^2 - 1)/12
+    for L in (2, 9, 1000):
+        m, v = O.variance(np.arange(L, dtype=np.float64)[None, :])
+        assert m[0] == pytest.approx((L - 1) / 2, rel=1e-14)
+        assert v[0] == pytest.approx((L * L - 1) / 12, rel=1e-13)
+    # two points a, b: variance ((a-b)/2)^2 (population, not sample)
+    m, v = O.variance(np.array([[1.0, 4.0]]))
+    assert m[0] == 2.5 and v[0] == 2.25
+
+
+def test_variance_shift_and_scale_laws():
+    x = RNG(61).standard_normal((3, 257))
+    m, v = O.variance(x)
+    m2, v2 = O.variance(x + 1e3)
+    np.testing.assert_allclose(m2, m + 1e3, rtol=1e-12)
+    np.testing.assert_allclose(v2, v, rtol=1e-9)
+    m3, v3 = O.variance(-2.5 * x)
+    np.testing.assert_allclose(m3, -2.5 * m, rtol=1e-12)
+    np.testing.assert_allclose(v3, 6.25 * v, rtol=1e-12)
+
+
+def test_variance_matches_library_float64():
+    x = RNG(62).standard_normal((7, 1234)) * 3 + 0.7
+    m, v = O.variance(x)
+    np.testing.assert_allclose(m, np.mean(x, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(v, np.var(x, axis=1), rtol=1e-12)             # ddof = 0
+    t = torch.from_numpy(x)
+    np.testing.assert_allclose(v, torch.var(t, dim=1, unbiased=False).numpy(), rtol=1e-12)
+
+
+def test_variance_fused_and_incremental_forms_equal_definition():
+    rng = RNG(63)
+    for L in (1, 2, 5, 16):
+        x = rng.standard_normal(L) * 2 + 5
+        m_ref, v_ref = O.variance(x[None, :])
+        # level-1 incremental: one element at a time
+        n, mean, m2 = O.variance_incremental([(1, float(a), 0.0) for a in x])
+        assert n == L
+        assert mean == pytest.approx(m_ref[0], rel=1e-12, abs=1e-14)
+        assert m2 / L == pytest.approx(v_ref[0], rel=1e-11, abs=1e-14)
+        # every split into segments (with an empty one in between), fused and incremental
+        for seg in (1, 2, 3, 5):
+            states = [O.variance_segment_state(x[lo:lo + seg]) for lo in range(0, L, seg)]
+            states.insert(1, O.variance_segment_state(x[:0]))
+            for fold in (O.variance_fused_levelk, O.variance_incremental):
+                n, mean, m2 = fold(states)
+                assert n == L
+                assert mean == pytest.approx(m_ref[0], rel=1e-12, abs=1e-14)
+                assert m2 / L == pytest.approx(v_ref[0], rel=1e-11, abs=1e-14)
+
+
+def test_variance_merge_is_order_free():
+    x = RNG(64).standard_normal(30)
+    parts = [O.variance_segment_state(x[a:b]) for a, b in ((0, 7), (7, 8), (8, 30))]
+    ref = O.variance_incremental(parts)
+    for perm in itertools.permutations(parts):
+        got = O.variance_incremental(list(perm))
+        assert got[0] == ref[0]
+        assert got[1] == pytest.approx(ref[1], rel=1e-12)
+        assert got[2] == pytest.approx(ref[2], rel=1e-12)
+
+
+# -------------------------------------------------------------- MoE routing
+def test_topk_desc_order_and_ties():
+    v = np.array([0.5, 2.0, 2.0, -1.0, 2.0, 0.5])
+    assert list(O.topk_desc(v, 4)) == [1, 2, 4, 0]          # ties: lower index first
+    assert list(O.topk_desc(v, 6)) == [1, 2, 4, 0, 5, 3]
+    assert list(O.topk_desc(v, 1)) == [1]
+
+
+def test_moe_routing_full_k_is_sorted_softmax():
+    rng = RNG(71)
+    x = rng.standard_normal((6, 40)); w = rng.standard_normal((40, 16))
+    prob, idx, p = O.moe_routing(x, w, 16)
+    np.testing.assert_allclose(prob.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+    assert np.all(np.diff(prob, axis=1) <= 0)
+    y = torch.softmax(torch.from_numpy(x @ w), dim=1).numpy()     # library special case
+    for i in range(6):
+        assert sorted(idx[i]) == list(range(16))
+        np.testing.assert_allclose(prob[i], y[i, idx[i]], rtol=1e-12)
+
+
+def test_moe_routing_matches_library_topk_and_scores_not_transposed():
+    rng = RNG(72)
+    S, hd, E, k = 9, 24, 32, 6
+    x = rng.standard_normal((S, hd)); w = rng.standard_normal((hd, E))
+    prob, idx, p = O.moe_routing(x, w, k)
+    # scores: p[i, e] = sum_c x[i, c] w[c, e], checked entry by entry
+    for (i, e) in ((0, 0), (3, 31), (8, 17)):
+        assert p[i, e] == pytest.approx(sum(x[i, c] * w[c, e] for c in range(hd)), rel=1e-12)
+    tv, ti = torch.topk(torch.softmax(torch.from_numpy(p), dim=1), k, dim=1)
+    np.testing.assert_array_equal(idx, ti.numpy())           # continuous data: no ties
+    np.testing.assert_allclose(prob, tv.numpy(), rtol=1e-12)
+
+
+def test_moe_routing_top1_closed_form():
+    # one dominant expert: p = (a, 0, ..., 0) -> prob = 1 / (1 + (E-1) e^{-a})
+    E, a = 8, 3.0
+    x = np.array([[1.0]]); w = np.zeros((1, E)); w[0, 5] = a
+    prob, idx, _ = O.moe_routing(x, w, 1)
+    assert idx[0, 0] == 5
+    assert prob[0, 0] == pytest.approx(1.0 / (1.0 + (E - 1) * math.exp(-a)), rel=1e-14)
+    # all scores equal: every prob 1/E, experts 0..k-1 in index order
+    prob, idx, _ = O.moe_routing(np.ones((1, 3)), np.ones((3, E)), 3)
+    assert list(idx[0]) == [0, 1, 2] and np.all(prob == 1.0 / E)
+
+
+def test_moe_routing_expert_permutation_equivariance():
+    rng = RNG(73)
+    x = rng.standard_normal((5, 12)); w = rng.standard_normal((12, 20))
+    perm = rng.permutation(20)
+    prob, idx, _ = O.moe_routing(x, w, 4)
+    prob_p, idx_p, _ = O.moe_routing(x, w[:, perm], 4)
+    np.testing.assert_allclose(prob_p, prob, rtol=1e-12)
+    np.testing.assert_array_equal(perm[idx_p], idx)
+
+
+def test_moe_routing_incremental_form_equals_definition():
+    rng = RNG(74)
+    x = rng.standard_normal((4, 10)); w = rng.standard_normal((10, 13))
+    for k in (1, 3, 13):
+        prob, idx, p = O.moe_routing(x, w, k)
+        for seg in (1, 2, 5, 13, 20):
+            for i in range(4):
+                pr, ix = O.moe_routing_incremental_row(p[i], k, seg)
+                np.testing.assert_array_equal(ix, idx[i])
+                np.testing.assert_allclose(pr, prob[i], rtol=1e-12)
+
+
+def test_topk_merge_is_associative_and_commutative():
+    rng = RNG(75)
+    v = rng.integers(0, 5, size=18).astype(np.float64)        # many ties on purpose
+    items = [(float(v[j]), j) for j in range(18)]
+    a, b, c = items[:5], items[5:11], items[11:]
+    top = lambda lst: O.topk_merge(lst, [], 4)
+    ref = O.topk_merge(items, [], 4)
+    assert [j for _, j in ref] == list(O.topk_desc(v, 4))
+    for (p, q, r) in itertools.permutations((a, b, c)):
+        assert O.topk_merge(O.topk_merge(top(p), top(q), 4), top(r), 4) == ref
+        assert O.topk_merge(top(p), O.topk_merge(top(q), top(r), 4), 4) == ref

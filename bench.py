@@ -8,6 +8,9 @@ input: every entry point of the library on its benchmark workload
   w2  rf_cascade_attention         bf16  B4 H32 L2048 d128, non-causal and causal
   w3  rf_cascade_attention_splitk + rf_merge_states   bf16 B16 Hq32 Hkv8 Lk32768 d128, S=64
   w4  rf_rmsnorm_gemm              bf16  4096 x 4096 x 4096
+After the timed steps the paper's further cascades are timed one kernel at a time
+(``further_cascades``; they are not part of a step):
+  x1  rf_variance                  f32   X[1024,32768]
 Inputs are generated on the device from fixed seeds before the timed region.
 The memory-bound workloads (w1, w3) rotate over three buffer sets so that the
 last-level cache cannot serve repeated reads.
@@ -41,7 +44,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--only", type=str, default="", help="comma list of w0..w4 (profiling aid); default all")
+    ap.add_argument("--only", type=str, default="",
+                    help="comma list of w0..w4 and x1.. (profiling aid); default all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 256 MiB -> 256 MiB copy kernel before the warmup "
@@ -61,7 +65,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4"}
+    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1"}
     W = I.WORKLOADS
     seed = lambda i: I.SEED_BASE + i
 
@@ -222,6 +226,39 @@ def main():
 
     dominant = max(rooflines, key=lambda r: r["us"]) if rooflines else None
 
+    # ------------------------------------------------ further cascades of the paper
+    # Timed after the step loop, each kernel alone: `steps` launches bracketed by HIP
+    # events one by one, inputs rotating over N_ROT buffer sets.
+    def time_launches(fn, n, warm):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i in range(n):
+            evs[i][0].record()
+            fn(warm + i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        ts = [a.elapsed_time(b) * 1e3 for a, b in evs]
+        return dict(avg=float(np.mean(ts)), med=float(np.median(ts)), min=float(np.min(ts)))
+
+    further = {}
+    if "x1" in only:
+        c = I.EXTRA_WORKLOADS["variance_v8"]
+        xs = [I.variance_inputs_device(seed(6) + 100 * r, c["bs"], c["l"], c["dtype"], c["mu"], c["sigma"], dev)
+              for r in range(N_ROT)]
+        mv = [(torch.empty(c["bs"], dtype=torch.float32, device=dev), torch.empty(c["bs"], dtype=torch.float32, device=dev))
+              for _ in range(N_ROT)]
+        d = time_launches(lambda i: rf.rf_variance(xs[i % N_ROT], *mv[i % N_ROT]), args.steps, args.warmup)
+        b = 4.0 * c["bs"] * c["l"] + 8.0 * c["bs"]
+        ach = b / (d["avg"] * 1e-6) / 1e9
+        further["x1_variance"] = dict(workload=c["name"], us_avg=round(d["avg"], 2), us_med=round(d["med"], 2),
+                                      us_min=round(d["min"], 2), bound="hbm", GBps=round(ach, 1),
+                                      frac=round(ach / PEAK_HBM_GBS, 4), algorithmic_bytes=b)
+        rooflines.append(dict(kernel="x1_variance", bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                              frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic.get("x1_variance"), us=round(d["avg"], 2)))
+        del xs, mv
+
     # -------------------------------------------- measured ceilings (context, not the peaks)
     def timed(fn, n):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -294,6 +331,7 @@ def main():
                                "decode_gqa_B16_Hq32_Hkv8_Lk32768_S64 split+merge, rmsnorm_gemm_4096^3",
                    "seeds": [I.SEED_BASE + i for i in range(5)]},
         "workloads": workloads,
+        "further_cascades": further,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]} if dominant else None,
         "rooflines": rooflines,
         "ceilings": ceilings,

@@ -98,6 +98,20 @@ RF_API int rf_describe_cascade(const char* entry, rf_stage* out, int cap);
 RF_API rf_status rf_safe_softmax(const rf_tensor* x, rf_tensor* y, int axis, rf_stream stream);
 
 /*
+ * Mean and population variance over the last axis (paper Appendix, evaluation on
+ * non-ML workloads): the cascade
+ *   m = (1/L) sum_l x[l];   var = (1/L) sum_l (x[l] - m)^2
+ * computed with one read of x.  The running state is (count, mean, M2) and is
+ * merged pairwise (Section 3.2, level-k fused expression, for this cascade).
+ *   x    : ndim 1..5, last axis contiguous and non-empty, f32 or bf16; leading
+ *          dims must be expressible with one row pitch.
+ *   mean, var : f32, contiguous, shape = x.shape without the last axis
+ *          (shape [1] when x is 1-D).
+ */
+RF_API rf_status rf_variance(const rf_tensor* x, rf_tensor* mean, rf_tensor* var,
+                             rf_stream stream);
+
+/*
  * Fused attention, single-segment strategy (Section 4.3; Appendix A.2):
  *   P = scale * Q K^T;  m = max_j P;  t = sum_j exp(P-m);  O = sum_j exp(P-m)/t * V[j]
  * with the running state (m, l, acc) kept on chip and acc divided by l once

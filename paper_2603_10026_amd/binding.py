@@ -29,6 +29,7 @@ ENTRY_POINTS = (
     "rf_cascade_attention_splitk",
     "rf_merge_states",
     "rf_rmsnorm_gemm",
+    "rf_variance",
     "rf_diag_copy",
     "rf_diag_mfma",
 )
@@ -83,6 +84,8 @@ def load_library():
     lib.rf_merge_states.argtypes = [P, P, P, P, ctypes.c_void_p]
     lib.rf_rmsnorm_gemm.restype = ctypes.c_int
     lib.rf_rmsnorm_gemm.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_void_p]
+    lib.rf_variance.restype = ctypes.c_int
+    lib.rf_variance.argtypes = [P, P, P, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.rf_diag_mfma.restype = ctypes.c_int
@@ -198,6 +201,20 @@ def rf_rmsnorm_gemm(x, g, w, eps=1e-6, y=None, stream=None):
     _check(lib.rf_rmsnorm_gemm(ctypes.byref(dx), ctypes.byref(dg), ctypes.byref(dw),
                                ctypes.byref(dy), float(eps), _stream(stream)), "rf_rmsnorm_gemm")
     return y
+
+
+def rf_variance(x, mean=None, var=None, stream=None):
+    """Mean and population variance over the last axis; returns (mean, var), fp32."""
+    lib = load_library()
+    oshape = tuple(x.shape[:-1]) if x.dim() > 1 else (1,)
+    if mean is None:
+        mean = torch.empty(oshape, dtype=torch.float32, device=x.device)
+    if var is None:
+        var = torch.empty(oshape, dtype=torch.float32, device=x.device)
+    dx, dm, dv = tensor_desc(x), tensor_desc(mean), tensor_desc(var)
+    _check(lib.rf_variance(ctypes.byref(dx), ctypes.byref(dm), ctypes.byref(dv), _stream(stream)),
+           "rf_variance")
+    return mean, var
 
 
 def rf_diag_copy(src, dst, stream=None):

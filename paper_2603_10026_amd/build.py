@@ -17,6 +17,7 @@ LIB = os.path.join(HERE, "librf.so")
 SOURCES = [
     "api.hip",
     "softmax.hip",
+    "variance.hip",
     "attention_f32.hip",
     "attention_bf16.hip",
     "attention_splitk.hip",

@@ -126,6 +126,7 @@ int rf_describe_cascade(const char* entry, rf_stage* out, int cap) {
   else if (!strcmp(entry, "rf_cascade_attention") || !strcmp(entry, "rf_cascade_attention_splitk") ||
            !strcmp(entry, "rf_merge_states")) { src = kAttention; n = 3; }
   else if (!strcmp(entry, "rf_rmsnorm_gemm")) { src = kRms; n = 2; }
+  else if (!strcmp(entry, "rf_variance")) { src = kRms; n = 2; }  // sum, then sum
   else return -1;
   if (out != nullptr)
     for (int i = 0; i < n && i < cap; ++i) out[i] = src[i];
@@ -155,6 +156,38 @@ rf_status rf_safe_softmax(const rf_tensor* x, rf_tensor* y, int axis, rf_stream 
                       (yp * es) % 16 == 0;
   hipError_t e = rf::launch_softmax(x->data, y->data, x->dtype == RF_BF16, rows, n, xp, yp, vec_ok,
                                     (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
+rf_status rf_variance(const rf_tensor* x, rf_tensor* mean, rf_tensor* var, rf_stream stream) {
+  rf_status st;
+  if ((st = check_tensor(x, 1, RF_MAX_DIMS)) != RF_OK) return st;
+  if ((st = check_tensor(mean, 1, RF_MAX_DIMS)) != RF_OK) return st;
+  if ((st = check_tensor(var, 1, RF_MAX_DIMS)) != RF_OK) return st;
+  if (mean->dtype != RF_F32 || var->dtype != RF_F32) return RF_ERR_UNSUPPORTED;
+  const int nd = x->ndim;
+  // outputs: x.shape without its last axis ([1] for a 1-D x), contiguous
+  if (!same_shape(mean, var)) return RF_ERR_INVALID_ARG;
+  if (nd == 1) {
+    if (mean->ndim != 1 || mean->shape[0] != 1) return RF_ERR_INVALID_ARG;
+  } else {
+    if (mean->ndim != nd - 1) return RF_ERR_INVALID_ARG;
+    for (int i = 0; i < nd - 1; ++i)
+      if (mean->shape[i] != x->shape[i]) return RF_ERR_INVALID_ARG;
+  }
+  if (!is_contiguous(mean) || !is_contiguous(var)) return RF_ERR_UNSUPPORTED;
+  const int64_t n = x->shape[nd - 1];
+  int64_t rows, xp;
+  if (!collapse_rows(x, &rows, &xp)) return RF_ERR_UNSUPPORTED;
+  if (rows == 0) return RF_OK;
+  if (n == 0) return RF_ERR_INVALID_ARG;  // the variance of nothing is not defined
+  if (x->data == nullptr || mean->data == nullptr || var->data == nullptr) return RF_ERR_INVALID_ARG;
+  if (x->stride[nd - 1] != 1 && n > 1) return RF_ERR_UNSUPPORTED;
+  if (rows > INT32_MAX) return RF_ERR_UNSUPPORTED;
+  const size_t es = esize(x->dtype);
+  const bool vec_ok = reinterpret_cast<uintptr_t>(x->data) % 16 == 0 && (xp * es) % 16 == 0;
+  hipError_t e = rf::launch_variance(x->data, x->dtype == RF_BF16, (float*)mean->data,
+                                     (float*)var->data, rows, n, xp, vec_ok, (hipStream_t)stream);
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 

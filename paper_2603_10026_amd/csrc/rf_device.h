@@ -36,6 +36,39 @@ __device__ __forceinline__ bf16_t to_bf16(float a) {
 }
 __device__ __forceinline__ float from_bf16(bf16_t a) { return __uint_as_float(((uint32_t)a) << 16); }
 
+// ---- element access by storage type (128-bit vectors) ---------------------
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+  static constexpr int kPerVec = 8;  // elements per 128-bit access
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(r[i]); f[2 * i + 1] = bf16_hi(r[i]); }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    return r;
+  }
+  static __device__ __forceinline__ float load(const bf16_t* p) { return from_bf16(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = to_bf16(v); }
+};
+template <> struct Elem<float> {
+  static constexpr int kPerVec = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float* f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(r[i]);
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(f[i]);
+    return r;
+  }
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+
 // ---- DPP lane exchange ----------------------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {

@@ -47,6 +47,10 @@ hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w,
                                     int K, int N, int64_t ldx, int64_t ldw, int64_t ldy,
                                     float eps, hipStream_t s);
 
+// Rows of length n (pitch in elements); mean, var: one float per row.
+hipError_t launch_variance(const void* x, bool is_bf16, float* mean, float* var, int64_t rows,
+                           int64_t n, int64_t x_pitch, bool vec_ok, hipStream_t s);
+
 // Measurement aids: a plain copy of `bytes` (multiple of 16) and an MFMA-only loop
 // (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
 // workgroups * 256 floats).

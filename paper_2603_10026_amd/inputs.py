@@ -37,6 +37,12 @@ WORKLOADS = {
             M=4096, K=4096, N=4096, eps=1e-6, w_sigma=0.02),
 }
 
+# Workloads of the paper's further cascades (its appendix tables), largest configurations.
+EXTRA_WORKLOADS = {
+    "variance_v8": dict(name="variance_f32_1024x32768", kind="variance", dtype="f32",
+                        bs=1024, l=32768, mu=1.0, sigma=2.0),
+}
+
 
 # --------------------------------------------------------------------------
 # bf16 storage helpers (host)
@@ -96,6 +102,13 @@ def rmsnorm_gemm_inputs(seed, M, K, N, w_sigma=0.02, dtype="bf16"):
     g = _store(rng.random(K, dtype=np.float32) + np.float32(0.5), dtype)
     w = _store(rng.standard_normal((K, N), dtype=np.float32) * np.float32(w_sigma), dtype)
     return x, g, w
+
+
+def variance_inputs(seed, bs, l, dtype="f32", mu=1.0, sigma=2.0):
+    """X[bs,l] i.i.d. N(mu, sigma^2); a non-zero mean makes sum(x^2) - (sum x)^2/L cancel."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal((bs, l), dtype=np.float32) * np.float32(sigma) + np.float32(mu)
+    return _store(x, dtype)
 
 
 def default_scale(d):
@@ -158,6 +171,15 @@ def softmax_inputs_device(seed, rows, n, sigma, dtype, device="cuda:0"):
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     return _randn_device(gen, (rows, n), dtype, device, sigma=sigma)
+
+
+def variance_inputs_device(seed, bs, l, dtype="f32", mu=1.0, sigma=2.0, device="cuda:0"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = torch.randn((bs, l), generator=gen, device=device, dtype=torch.float32)
+    x.mul_(sigma).add_(mu)
+    return x.to(_torch_dtype(dtype))
 
 
 def rmsnorm_gemm_inputs_device(seed, M, K, N, w_sigma=0.02, dtype="bf16", device="cuda:0"):

@@ -133,6 +133,20 @@ def test_rmsnorm_gemm_validation(lib):
     assert f(_r(_desc([0, 128], data=None)), _r(g), _r(w), _r(_desc([0, 64], data=None)), 1e-6, None) == B.RF_OK
 
 
+def test_variance_validation(lib):
+    F32 = B.RF_F32
+    x, m, v = _desc([8, 256], F32), _desc([8], F32), _desc([8], F32)
+    f = lib.rf_variance
+    assert f(None, _r(m), _r(v), None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(_desc([7], F32)), _r(_desc([7], F32)), None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(_desc([8])), _r(v), None) == B.RF_ERR_UNSUPPORTED          # outputs must be f32
+    assert f(_r(_desc([8, 0], F32)), _r(m), _r(v), None) == B.RF_ERR_INVALID_ARG  # empty rows
+    assert f(_r(_desc([8, 256], F32, stride=[512, 2])), _r(m), _r(v), None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([8, 256], F32, data=None)), _r(m), _r(v), None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(_desc([0, 256], F32, data=None)), _r(_desc([0], F32, data=None)), _r(_desc([0], F32, data=None)), None) == B.RF_OK
+    assert B.describe_cascade("rf_variance") == [(2, 1), (2, 1)]                  # (sum, *) twice
+
+
 def test_binding_descriptor_from_torch_tensor():
     t = torch.zeros((3, 4, 8), dtype=torch.bfloat16)[:, 1:3]
     d = B.tensor_desc(t)

@@ -264,3 +264,53 @@ def test_rmsnorm_gemm_row_scales_and_pitched_output(rf):
     for i in (0, 1, 3):
         assert np.max(np.abs(out[i] - ref[i])) <= 2e-2 * np.max(np.abs(ref[i]))
     assert np.all(out[2] == 0.0)
+
+
+# ----------------------------------------------------------------- variance
+# Outputs are fp32 and the state arithmetic is fp32 whatever the storage type of x
+# (bf16 inputs are exact for both sides), so the fp32 rule applies to both.
+@pytest.mark.parametrize("dtype,bs,l", [
+    ("f32", 3, 8192), ("f32", 2, 32768), ("f32", 5, 1000), ("f32", 4, 4099), ("f32", 7, 3), ("f32", 2, 1),
+    ("f32", 1, 70001), ("bf16", 3, 8192), ("bf16", 4, 1003), ("bf16", 2, 9), ("bf16", 130, 2048),
+])
+def test_variance_shapes(rf, dtype, bs, l):
+    say(f"variance {dtype} bs={bs} l={l}")
+    x = I.variance_inputs(I.SEED_BASE + 6, bs, l, dtype)
+    mean, var = rf.rf_variance(I.to_torch(x, dtype, DEV))
+    torch.cuda.synchronize()
+    m_ref, v_ref = O.variance(x)
+    check(mean, m_ref, "f32", "variance mean")
+    check(var, v_ref, "f32", "variance var")
+
+
+def test_variance_large_offset_unaligned_and_pitched(rf):
+    say("variance: mean >> spread, unaligned rows, pitched rows, 1-D, 3-D")
+    # mean 1000, sigma 0.5: sum(x^2) - (sum x)^2/L would lose every digit in fp32
+    x = I.variance_inputs(77, 4, 5000, "f32", mu=1000.0, sigma=0.5)
+    mean, var = rf.rf_variance(I.to_torch(x, "f32", DEV))
+    m_ref, v_ref = O.variance(x)
+    check(mean, m_ref, "f32", "variance mean (offset)")
+    out = I.to_numpy(var)
+    assert np.max(np.abs(out - v_ref)) <= 2e-4 * np.max(v_ref), (out, v_ref)   # input rounding at 1000 is 6e-5
+    # constant rows: variance exactly 0
+    c = torch.full((3, 777), 2.5, device=DEV)
+    mean, var = rf.rf_variance(c)
+    assert torch.all(mean == 2.5) and torch.all(var == 0.0)
+    # rows at an odd element offset (no 128-bit loads) and with a pitch
+    x = I.variance_inputs(78, 6, 1001, "f32")
+    big = torch.zeros((6, 1030), device=DEV)
+    big[:, 3:1004] = I.to_torch(x, "f32", DEV)
+    mean, var = rf.rf_variance(big[:, 3:1004])
+    m_ref, v_ref = O.variance(x)
+    check(mean, m_ref, "f32", "variance mean (unaligned, pitched)")
+    check(var, v_ref, "f32", "variance var (unaligned, pitched)")
+    # 1-D and 3-D inputs
+    mean, var = rf.rf_variance(I.to_torch(x[0], "f32", DEV))
+    assert mean.shape == (1,)
+    check(var, v_ref[:1], "f32", "variance var (1-D)")
+    x3 = I.variance_inputs(79, 6, 512, "bf16").reshape(2, 3, 512)
+    mean, var = rf.rf_variance(I.to_torch(x3, "bf16", DEV))
+    m_ref, v_ref = O.variance(x3)
+    check(mean, m_ref, "f32", "variance mean (3-D)")
+    check(var, v_ref, "f32", "variance var (3-D)")
+    torch.cuda.synchronize()

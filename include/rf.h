@@ -31,6 +31,7 @@
 #ifndef RF_H_
 #define RF_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -52,7 +53,7 @@ typedef enum {
   RF_ERR_LAUNCH = 5       /* the HIP runtime rejected a launch                  */
 } rf_status;
 
-typedef enum { RF_F32 = 0, RF_BF16 = 1 } rf_dtype;
+typedef enum { RF_F32 = 0, RF_BF16 = 1, RF_I32 = 2 } rf_dtype;
 
 /* (+)_i and (x)_i of Table 1. */
 typedef enum { RF_RED_MAX = 0, RF_RED_MIN = 1, RF_RED_SUM = 2 } rf_reduce_op;
@@ -110,6 +111,28 @@ RF_API rf_status rf_safe_softmax(const rf_tensor* x, rf_tensor* y, int axis, rf_
  */
 RF_API rf_status rf_variance(const rf_tensor* x, rf_tensor* mean, rf_tensor* var,
                              rf_stream stream);
+
+/*
+ * MoE routing (Appendix A.2, "MoE routing"): the scores GEMM feeding the cascade
+ *   p[e] = sum_c x[c] w[c,e];  m = max_e p[e];  t = sum_e exp(p[e]-m);  s = TopK_e p[e]
+ * with output exp(s - m) / t, the softmax probability of each selected expert.
+ * TopK acts on the raw scores (softmax keeps their order); the k results are in
+ * descending order of score, equal scores in ascending order of expert index.
+ * The contraction axis is split over workgroups (multi-segment strategy,
+ * Section 4.3); fp32 partial scores pass through `workspace`.
+ *   x    : [S, hd] bf16, tokens.            hd % 128 == 0.
+ *   w    : [hd, E] bf16, router weights.    E in {32, 64, 128}.
+ *   topk : 1 .. min(E, 16).
+ *   prob : [S, topk] f32;  idx : [S, topk] i32 (expert indices).
+ *   workspace : device memory, 16-byte aligned, at least
+ *          rf_moe_routing_workspace_bytes(S, hd, E) bytes; contents need no
+ *          initialisation and are undefined afterwards.  Too small or misaligned:
+ *          RF_ERR_WORKSPACE.  Concurrent calls must not share a workspace.
+ */
+RF_API size_t rf_moe_routing_workspace_bytes(int64_t S, int64_t hd, int64_t E);
+RF_API rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
+                                rf_tensor* idx, void* workspace, size_t workspace_bytes,
+                                rf_stream stream);
 
 /*
  * Fused attention, single-segment strategy (Section 4.3; Appendix A.2):

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librf.so")
 
 RF_OK = 0
 RF_ERR_INVALID_ARG, RF_ERR_UNSUPPORTED, RF_ERR_ALIGNMENT, RF_ERR_WORKSPACE, RF_ERR_LAUNCH = 1, 2, 3, 4, 5
-RF_F32, RF_BF16 = 0, 1
+RF_F32, RF_BF16, RF_I32 = 0, 1, 2
 RF_MAX_DIMS = 5
 
 ENTRY_POINTS = (
@@ -30,6 +30,8 @@ ENTRY_POINTS = (
     "rf_merge_states",
     "rf_rmsnorm_gemm",
     "rf_variance",
+    "rf_moe_routing_workspace_bytes",
+    "rf_moe_routing",
     "rf_diag_copy",
     "rf_diag_mfma",
 )
@@ -86,6 +88,10 @@ def load_library():
     lib.rf_rmsnorm_gemm.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_void_p]
     lib.rf_variance.restype = ctypes.c_int
     lib.rf_variance.argtypes = [P, P, P, ctypes.c_void_p]
+    lib.rf_moe_routing_workspace_bytes.restype = ctypes.c_size_t
+    lib.rf_moe_routing_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+    lib.rf_moe_routing.restype = ctypes.c_int
+    lib.rf_moe_routing.argtypes = [P, P, ctypes.c_int, P, P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.rf_diag_mfma.restype = ctypes.c_int
@@ -108,7 +114,7 @@ def describe_cascade(entry):
     return [(buf[i].reduce, buf[i].combine) for i in range(n)]
 
 
-_DTYPES = {torch.float32: RF_F32, torch.bfloat16: RF_BF16}
+_DTYPES = {torch.float32: RF_F32, torch.bfloat16: RF_BF16, torch.int32: RF_I32}
 
 
 def tensor_desc(t):
@@ -215,6 +221,30 @@ def rf_variance(x, mean=None, var=None, stream=None):
     _check(lib.rf_variance(ctypes.byref(dx), ctypes.byref(dm), ctypes.byref(dv), _stream(stream)),
            "rf_variance")
     return mean, var
+
+
+def moe_routing_workspace_bytes(S, hd, E):
+    return int(load_library().rf_moe_routing_workspace_bytes(int(S), int(hd), int(E)))
+
+
+def rf_moe_routing(x, w, topk, prob=None, idx=None, workspace=None, stream=None):
+    """Router scores -> softmax -> top-k; returns (prob [S,topk] f32, idx [S,topk] i32).
+    ``workspace``: a uint8 device tensor of at least moe_routing_workspace_bytes(...) bytes
+    (allocated here when omitted)."""
+    lib = load_library()
+    S, hd = x.shape
+    E = w.shape[1]
+    if prob is None:
+        prob = torch.empty((S, topk), dtype=torch.float32, device=x.device)
+    if idx is None:
+        idx = torch.empty((S, topk), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(moe_routing_workspace_bytes(S, hd, E), 16), dtype=torch.uint8, device=x.device)
+    dx, dw, dp, di = tensor_desc(x), tensor_desc(w), tensor_desc(prob), tensor_desc(idx)
+    _check(lib.rf_moe_routing(ctypes.byref(dx), ctypes.byref(dw), int(topk), ctypes.byref(dp), ctypes.byref(di),
+                              ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                              _stream(stream)), "rf_moe_routing")
+    return prob, idx
 
 
 def rf_diag_copy(src, dst, stream=None):

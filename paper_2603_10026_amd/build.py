@@ -18,6 +18,7 @@ SOURCES = [
     "api.hip",
     "softmax.hip",
     "variance.hip",
+    "moe_routing.hip",
     "attention_f32.hip",
     "attention_bf16.hip",
     "attention_splitk.hip",

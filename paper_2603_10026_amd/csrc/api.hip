@@ -8,14 +8,17 @@
 
 namespace {
 
-inline size_t esize(rf_dtype t) { return t == RF_BF16 ? 2 : 4; }
-inline bool dtype_ok(rf_dtype t) { return t == RF_F32 || t == RF_BF16; }
+inline size_t esize(rf_dtype t) { return t == RF_BF16 ? 2 : 4; }  // f32 and i32: 4
+inline bool dtype_ok(rf_dtype t, bool allow_i32) {
+  return t == RF_F32 || t == RF_BF16 || (allow_i32 && t == RF_I32);
+}
 
 // Structural checks common to every tensor argument.
-rf_status check_tensor(const rf_tensor* t, int ndim_min, int ndim_max) {
+// (integer tensors are accepted only where an entry point asks for them)
+rf_status check_tensor(const rf_tensor* t, int ndim_min, int ndim_max, bool allow_i32 = false) {
   if (t == nullptr) return RF_ERR_INVALID_ARG;
   if (t->ndim < ndim_min || t->ndim > ndim_max) return RF_ERR_INVALID_ARG;
-  if (!dtype_ok(t->dtype)) return RF_ERR_UNSUPPORTED;
+  if (!dtype_ok(t->dtype, allow_i32)) return RF_ERR_UNSUPPORTED;
   for (int i = 0; i < t->ndim; ++i) {
     if (t->shape[i] < 0 || t->stride[i] < 0) return RF_ERR_INVALID_ARG;
   }
@@ -120,6 +123,9 @@ int rf_describe_cascade(const char* entry, rf_stage* out, int cap) {
   static const rf_stage kAttention[] = {
       {RF_RED_MAX, RF_COMB_ADD}, {RF_RED_SUM, RF_COMB_MUL}, {RF_RED_SUM, RF_COMB_MUL}};
   static const rf_stage kRms[] = {{RF_RED_SUM, RF_COMB_MUL}, {RF_RED_SUM, RF_COMB_MUL}};
+  // max, sum of exponentials, TopK (a max-type reduction, Table 1)
+  static const rf_stage kRouting[] = {
+      {RF_RED_MAX, RF_COMB_ADD}, {RF_RED_SUM, RF_COMB_MUL}, {RF_RED_MAX, RF_COMB_ADD}};
   const rf_stage* src = nullptr;
   int n = 0;
   if (!strcmp(entry, "rf_safe_softmax")) { src = kSoftmax; n = 2; }
@@ -127,6 +133,7 @@ int rf_describe_cascade(const char* entry, rf_stage* out, int cap) {
            !strcmp(entry, "rf_merge_states")) { src = kAttention; n = 3; }
   else if (!strcmp(entry, "rf_rmsnorm_gemm")) { src = kRms; n = 2; }
   else if (!strcmp(entry, "rf_variance")) { src = kRms; n = 2; }  // sum, then sum
+  else if (!strcmp(entry, "rf_moe_routing")) { src = kRouting; n = 3; }
   else return -1;
   if (out != nullptr)
     for (int i = 0; i < n && i < cap; ++i) out[i] = src[i];
@@ -188,6 +195,48 @@ rf_status rf_variance(const rf_tensor* x, rf_tensor* mean, rf_tensor* var, rf_st
   const bool vec_ok = reinterpret_cast<uintptr_t>(x->data) % 16 == 0 && (xp * es) % 16 == 0;
   hipError_t e = rf::launch_variance(x->data, x->dtype == RF_BF16, (float*)mean->data,
                                      (float*)var->data, rows, n, xp, vec_ok, (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
+size_t rf_moe_routing_workspace_bytes(int64_t S, int64_t hd, int64_t E) {
+  if (S <= 0 || hd <= 0 || E <= 0 || S > INT32_MAX || hd > INT32_MAX) return 0;
+  return (size_t)rf::moe_num_slices((int)S, (int)hd) * (size_t)S * (size_t)E * sizeof(float);
+}
+
+rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
+                         rf_tensor* idx, void* workspace, size_t workspace_bytes,
+                         rf_stream stream) {
+  rf_status st;
+  if ((st = check_tensor(x, 2, 2)) != RF_OK) return st;
+  if ((st = check_tensor(w, 2, 2)) != RF_OK) return st;
+  if ((st = check_tensor(prob, 2, 2)) != RF_OK) return st;
+  if ((st = check_tensor(idx, 2, 2, true)) != RF_OK) return st;
+  if (x->dtype != RF_BF16 || w->dtype != RF_BF16 || prob->dtype != RF_F32 || idx->dtype != RF_I32)
+    return RF_ERR_UNSUPPORTED;
+  const int64_t S = x->shape[0], hd = x->shape[1], E = w->shape[1];
+  if (w->shape[0] != hd) return RF_ERR_INVALID_ARG;
+  if (topk < 1 || topk > E) return RF_ERR_INVALID_ARG;
+  if (prob->shape[0] != S || prob->shape[1] != topk || !same_shape(prob, idx)) return RF_ERR_INVALID_ARG;
+  if (S == 0) return RF_OK;
+  if (hd == 0 || hd % 128 != 0 || (E != 32 && E != 64 && E != 128) || topk > 16)
+    return RF_ERR_UNSUPPORTED;
+  if (S > INT32_MAX || hd > INT32_MAX) return RF_ERR_UNSUPPORTED;
+  for (const rf_tensor* t : {x, w, (const rf_tensor*)prob, (const rf_tensor*)idx})
+    if (t->shape[1] > 1 && t->stride[1] != 1) return RF_ERR_UNSUPPORTED;
+  if (x->data == nullptr || w->data == nullptr || prob->data == nullptr || idx->data == nullptr)
+    return RF_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(w)) return RF_ERR_ALIGNMENT;
+  if (reinterpret_cast<uintptr_t>(prob->data) % 4 != 0 || reinterpret_cast<uintptr_t>(idx->data) % 4 != 0)
+    return RF_ERR_ALIGNMENT;
+  if (S * x->stride[0] * 2 >= ((int64_t)1 << 32) || 128 * w->stride[0] * 2 >= ((int64_t)1 << 32))
+    return RF_ERR_UNSUPPORTED;
+  if (workspace == nullptr || reinterpret_cast<uintptr_t>(workspace) % 16 != 0 ||
+      workspace_bytes < rf_moe_routing_workspace_bytes(S, hd, E))
+    return RF_ERR_WORKSPACE;
+  hipError_t e = rf::launch_moe_routing(x->data, w->data, (int)S, (int)hd, (int)E, topk,
+                                        x->stride[0], w->stride[0], (float*)prob->data,
+                                        (int32_t*)idx->data, prob->stride[0], idx->stride[0],
+                                        (float*)workspace, (hipStream_t)stream);
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 

@@ -51,6 +51,14 @@ hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w,
 hipError_t launch_variance(const void* x, bool is_bf16, float* mean, float* var, int64_t rows,
                            int64_t n, int64_t x_pitch, bool vec_ok, hipStream_t s);
 
+// x [S,hd], w [hd,E] bf16; prob, idx [S,topk] with row pitches ldp, ldi; part: fp32
+// workspace of moe_num_slices(S, hd) * S * E floats.  hd % 128 == 0, E in {32, 64, 128},
+// 1 <= topk <= 16.
+int moe_num_slices(int S, int hd);
+hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E, int topk,
+                              int64_t ldx, int64_t ldw, float* prob, int32_t* idx, int64_t ldp,
+                              int64_t ldi, float* part, hipStream_t s);
+
 // Measurement aids: a plain copy of `bytes` (multiple of 16) and an MFMA-only loop
 // (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
 // workgroups * 256 floats).

@@ -39,6 +39,10 @@ WORKLOADS = {
 
 # Workloads of the paper's further cascades (its appendix tables), largest configurations.
 EXTRA_WORKLOADS = {
+    "moe_routing_r5": dict(name="moe_routing_bf16_s2048_hd8192_en64_top8", kind="moe_routing", dtype="bf16",
+                           S=2048, hd=8192, E=64, topk=8, score_sigma=1.5),
+    "moe_routing_r8": dict(name="moe_routing_bf16_s2048_hd4096_en128_top8", kind="moe_routing", dtype="bf16",
+                           S=2048, hd=4096, E=128, topk=8, score_sigma=1.5),
     "variance_v8": dict(name="variance_f32_1024x32768", kind="variance", dtype="f32",
                         bs=1024, l=32768, mu=1.0, sigma=2.0),
 }
@@ -111,6 +115,15 @@ def variance_inputs(seed, bs, l, dtype="f32", mu=1.0, sigma=2.0):
     return _store(x, dtype)
 
 
+def moe_routing_inputs(seed, S, hd, E, score_sigma=1.5, dtype="bf16"):
+    """Tokens X[S,hd] ~ N(0,1), router weights W[hd,E] ~ N(0, score_sigma^2 / hd): scores have
+    standard deviation score_sigma, so the softmax over experts is neither flat nor one-hot."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = _store(rng.standard_normal((S, hd), dtype=np.float32), dtype)
+    w = _store(rng.standard_normal((hd, E), dtype=np.float32) * np.float32(score_sigma / math.sqrt(hd)), dtype)
+    return x, w
+
+
 def default_scale(d):
     return 1.0 / math.sqrt(d)
 
@@ -180,6 +193,15 @@ def variance_inputs_device(seed, bs, l, dtype="f32", mu=1.0, sigma=2.0, device="
     x = torch.randn((bs, l), generator=gen, device=device, dtype=torch.float32)
     x.mul_(sigma).add_(mu)
     return x.to(_torch_dtype(dtype))
+
+
+def moe_routing_inputs_device(seed, S, hd, E, score_sigma=1.5, dtype="bf16", device="cuda:0"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = _randn_device(gen, (S, hd), dtype, device)
+    w = _randn_device(gen, (hd, E), dtype, device, sigma=score_sigma / math.sqrt(hd))
+    return x, w
 
 
 def rmsnorm_gemm_inputs_device(seed, M, K, N, w_sigma=0.02, dtype="bf16", device="cuda:0"):

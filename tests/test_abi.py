@@ -147,6 +147,35 @@ def test_variance_validation(lib):
     assert B.describe_cascade("rf_variance") == [(2, 1), (2, 1)]                  # (sum, *) twice
 
 
+def test_moe_routing_validation(lib):
+    F32, I32 = B.RF_F32, B.RF_I32
+    x, w = _desc([64, 256]), _desc([256, 64])
+    p, i = _desc([64, 4], F32), _desc([64, 4], I32)
+    f = lib.rf_moe_routing
+    need = lib.rf_moe_routing_workspace_bytes(64, 256, 64)
+    assert need >= 64 * 64 * 4 and need % (64 * 64 * 4) == 0
+    ws = ctypes.c_void_p(0x10000)
+    assert f(None, _r(w), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(_desc([128, 64])), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(w), 0, _r(p), _r(i), ws, need, None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(x), _r(w), 5, _r(p), _r(i), ws, need, None) == B.RF_ERR_INVALID_ARG       # outputs are [64, 4]
+    assert f(_r(x), _r(w), 4, _r(p), _r(_desc([64, 4], F32)), ws, need, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([64, 256], F32)), _r(w), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([64, 192])), _r(_desc([192, 64])), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(x), _r(_desc([256, 48])), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_UNSUPPORTED
+    p17, i17 = _desc([64, 17], F32), _desc([64, 17], I32)
+    assert f(_r(x), _r(w), 17, _r(p17), _r(i17), ws, need, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(_desc([64, 256], data=0x1008)), _r(w), 4, _r(p), _r(i), ws, need, None) == B.RF_ERR_ALIGNMENT
+    assert f(_r(x), _r(w), 4, _r(p), _r(i), None, need, None) == B.RF_ERR_WORKSPACE
+    assert f(_r(x), _r(w), 4, _r(p), _r(i), ws, need - 1, None) == B.RF_ERR_WORKSPACE
+    assert f(_r(x), _r(w), 4, _r(p), _r(i), ctypes.c_void_p(0x10004), need, None) == B.RF_ERR_WORKSPACE
+    # an integer tensor where a floating one is expected is refused, not reinterpreted
+    assert lib.rf_safe_softmax(_r(_desc([4, 64], I32)), _r(_desc([4, 64], I32)), -1, None) == B.RF_ERR_UNSUPPORTED
+    e0, p0, i0 = _desc([0, 256], data=None), _desc([0, 4], F32, data=None), _desc([0, 4], I32, data=None)
+    assert f(_r(e0), _r(w), 4, _r(p0), _r(i0), None, 0, None) == B.RF_OK
+    assert B.describe_cascade("rf_moe_routing") == [(0, 0), (2, 1), (0, 0)]      # max, sum, top-k (max-type)
+
+
 def test_binding_descriptor_from_torch_tensor():
     t = torch.zeros((3, 4, 8), dtype=torch.bfloat16)[:, 1:3]
     d = B.tensor_desc(t)

@@ -314,3 +314,83 @@ def test_variance_large_offset_unaligned_and_pitched(rf):
     check(mean, m_ref, "f32", "variance mean (3-D)")
     check(var, v_ref, "f32", "variance var (3-D)")
     torch.cuda.synchronize()
+
+
+# -------------------------------------------------------------- MoE routing
+def check_routing(prob, idx, x, w, topk, what, min_exact=0.9):
+    """GPU routing against the fp64 oracle.  The scores are accumulated in fp32 on the GPU, so
+    two experts whose fp64 scores differ by less than that arithmetic's error may be ordered
+    either way: what is unique is compared exactly, the rest is checked to be valid."""
+    prob = I.to_numpy(prob)
+    idx = idx.detach().cpu().numpy().astype(np.int64)
+    p_ref, i_ref, p = O.moe_routing(x, w, topk)
+    S, E = p.shape
+    assert prob.shape == (S, topk) and idx.shape == (S, topk)
+    assert np.all(np.isfinite(prob))
+    assert np.all((idx >= 0) & (idx < E)), f"{what}: expert index out of range"
+    delta = 4e-6 * max(1.0, float(np.max(np.abs(p))))          # fp32 accumulation error of a score
+    m = p.max(axis=1, keepdims=True)
+    soft = np.exp(p - m) / np.exp(p - m).sum(axis=1, keepdims=True)
+    exact = 0
+    for i in range(S):
+        sel = idx[i]
+        assert len(set(sel.tolist())) == topk, f"{what}: row {i} selects an expert twice"
+        ps = p[i, sel]
+        assert np.all(ps[:-1] >= ps[1:] - delta), f"{what}: row {i} not in descending order"
+        rest = np.delete(p[i], sel)
+        if rest.size:
+            assert rest.max() <= ps[-1] + delta, f"{what}: row {i} misses a larger score"
+        # decisions that the arithmetic cannot flip must match the oracle exactly
+        srt = np.sort(p[i])[::-1][:topk + 1]
+        if np.all(srt[:-1] - srt[1:] > 2 * delta):
+            assert np.array_equal(sel, i_ref[i]), f"{what}: row {i}: {sel} != {i_ref[i]}"
+            exact += 1
+        # probabilities of the experts it chose
+        np.testing.assert_allclose(prob[i], soft[i, sel], rtol=2e-4, atol=1e-7,
+                                   err_msg=f"{what}: row {i} probabilities")
+    err = float(np.max(np.abs(np.sort(prob, axis=1) - np.sort(p_ref, axis=1))))
+    print(f"        {what}: rows with margin-safe decisions {exact}/{S}, max|prob err|={err:.2e}", flush=True)
+    assert exact >= min_exact * S
+    assert err <= 1e-5 * float(np.max(p_ref)) + 1e-7
+
+
+@pytest.mark.parametrize("S,hd,E,topk", [
+    (128, 256, 64, 6), (100, 128, 32, 1), (300, 768, 128, 1), (64, 1024, 128, 8), (257, 512, 64, 8),
+    (1, 128, 128, 16), (70, 2560, 64, 6), (33, 384, 32, 16),
+])
+def test_moe_routing_shapes(rf, S, hd, E, topk):
+    say(f"moe_routing S{S} hd{hd} E{E} top{topk}")
+    x, w = I.moe_routing_inputs(I.SEED_BASE + 5, S, hd, E)
+    prob, idx = rf.rf_moe_routing(I.to_torch(x, "bf16", DEV), I.to_torch(w, "bf16", DEV), topk)
+    torch.cuda.synchronize()
+    check_routing(prob, idx, x, w, topk, "moe_routing")
+
+
+def test_moe_routing_exact_ties_and_pitched_outputs(rf):
+    say("moe_routing: exactly representable scores (many exact ties), pitched outputs, reused workspace")
+    # x in {-1, 0, 1} and w in multiples of 1/4: every partial sum is exact in fp32 in any
+    # order, so the GPU scores equal the fp64 ones bit for bit and ties are exact ties.
+    S, hd, E, topk = 96, 256, 64, 8
+    rng = np.random.Generator(np.random.PCG64(501))
+    x = rng.integers(-1, 2, size=(S, hd)).astype(np.float32)
+    w = rng.integers(-2, 3, size=(hd, E)).astype(np.float32) * 0.25
+    w[:, 40] = w[:, 3]            # duplicated experts on top of the accidental ties
+    w[:, 18] = w[:, 17]
+    w[:, 60] = w[:, 17]
+    x[5] = 0.0                    # all scores equal: experts 0..k-1, probability 1/E each
+    ws = torch.empty(rf.moe_routing_workspace_bytes(S, hd, E), dtype=torch.uint8, device=DEV)
+    pbig = torch.zeros((S, 2 * topk), dtype=torch.float32, device=DEV)
+    ibig = torch.full((S, 2 * topk), -7, dtype=torch.int32, device=DEV)
+    for rep in range(2):          # the second call reuses the workspace as the first left it
+        rf.rf_moe_routing(I.to_torch(x, "bf16", DEV), I.to_torch(w, "bf16", DEV), topk,
+                          prob=pbig[:, topk:], idx=ibig[:, :topk], workspace=ws)
+    torch.cuda.synchronize()
+    assert float(pbig[:, :topk].abs().max()) == 0.0 and int((ibig[:, topk:] != -7).sum()) == 0
+    prob, idx = I.to_numpy(pbig[:, topk:]), ibig[:, :topk].cpu().numpy().astype(np.int64)
+    p_ref, i_ref, p = O.moe_routing(x, w, topk)
+    n_ties = sum(len(set(np.sort(p[i])[::-1][:topk + 1].tolist())) < topk + 1 for i in range(S))
+    print(f"        rows with a tie among their top {topk + 1} scores: {n_ties}/{S}", flush=True)
+    assert n_ties > S // 4
+    np.testing.assert_array_equal(idx, i_ref)                 # bit-exact decisions, ties included
+    np.testing.assert_allclose(prob, p_ref, rtol=2e-5, atol=1e-8)
+    assert list(idx[5]) == list(range(topk)) and np.all(prob[5] == np.float32(1.0 / E))

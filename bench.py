@@ -11,6 +11,7 @@ input: every entry point of the library on its benchmark workload
 After the timed steps the paper's further cascades are timed one kernel at a time
 (``further_cascades``; they are not part of a step):
   x1  rf_variance                  f32   X[1024,32768]
+  x2  rf_moe_routing               bf16  tokens 2048; hd 8192 x 64 experts, hd 4096 x 128 experts; top 8
 Inputs are generated on the device from fixed seeds before the timed region.
 The memory-bound workloads (w1, w3) rotate over three buffer sets so that the
 last-level cache cannot serve repeated reads.
@@ -65,7 +66,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1"}
+    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1", "x2"}
     W = I.WORKLOADS
     seed = lambda i: I.SEED_BASE + i
 
@@ -258,6 +259,33 @@ def main():
         rooflines.append(dict(kernel="x1_variance", bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                               frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic.get("x1_variance"), us=round(d["avg"], 2)))
         del xs, mv
+    if "x2" in only:
+        for key in ("moe_routing_r5", "moe_routing_r8"):
+            c = I.EXTRA_WORKLOADS[key]
+            sets = []
+            for r in range(N_ROT):
+                xx, ww = I.moe_routing_inputs_device(seed(5) + 100 * r, c["S"], c["hd"], c["E"], c["score_sigma"], "bf16", dev)
+                sets.append(dict(x=xx, w=ww, p=torch.empty((c["S"], c["topk"]), dtype=torch.float32, device=dev),
+                                 i=torch.empty((c["S"], c["topk"]), dtype=torch.int32, device=dev)))
+            ws = torch.empty(rf.moe_routing_workspace_bytes(c["S"], c["hd"], c["E"]), dtype=torch.uint8, device=dev)
+
+            def route(i, sets=sets, ws=ws, c=c):
+                t = sets[i % N_ROT]
+                rf.rf_moe_routing(t["x"], t["w"], c["topk"], prob=t["p"], idx=t["i"], workspace=ws)
+
+            d = time_launches(route, args.steps, args.warmup)
+            # algorithmic bytes: tokens and router weights read once, results written once
+            b = 2.0 * c["S"] * c["hd"] + 2.0 * c["hd"] * c["E"] + 8.0 * c["S"] * c["topk"]
+            ach = b / (d["avg"] * 1e-6) / 1e9
+            label = "x2_" + key
+            further[label] = dict(workload=c["name"], us_avg=round(d["avg"], 2), us_med=round(d["med"], 2),
+                                  us_min=round(d["min"], 2), bound="hbm", GBps=round(ach, 1),
+                                  frac=round(ach / PEAK_HBM_GBS, 4), algorithmic_bytes=b,
+                                  workspace_bytes=ws.numel(),
+                                  note="two launches (scores, cascade) timed together; latency-bound at this size")
+            rooflines.append(dict(kernel=label, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                                  frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic.get(label), us=round(d["avg"], 2)))
+            del sets, ws
 
     # -------------------------------------------- measured ceilings (context, not the peaks)
     def timed(fn, n):

@@ -152,3 +152,40 @@ def test_workload4_rmsnorm_gemm_full(rf):
     idx = torch.from_numpy(rows).to(DEV)
     ref = O.rmsnorm_gemm(I.to_numpy(x[idx]), I.to_numpy(g), I.to_numpy(w), c["eps"])
     check_rows(I.to_numpy(y[idx]), ref, 2e-2, "rmsnorm_gemm rows", row_tol=2e-2)
+
+
+def test_variance_full(rf):
+    c = I.EXTRA_WORKLOADS["variance_v8"]
+    say(c["name"])
+    x = I.variance_inputs_device(I.SEED_BASE + 6, c["bs"], c["l"], c["dtype"], c["mu"], c["sigma"], DEV)
+    mean, var = rf.rf_variance(x)
+    torch.cuda.synchronize()
+    m_ref, v_ref = O.variance(I.to_numpy(x))                 # every row: the oracle takes seconds
+    check_rows(I.to_numpy(mean)[:, None], m_ref[:, None], 1e-5, "variance mean")
+    check_rows(I.to_numpy(var)[:, None], v_ref[:, None], 1e-5, "variance var", row_tol=1e-5)
+
+
+@pytest.mark.parametrize("key", ["moe_routing_r5", "moe_routing_r8"])
+def test_moe_routing_full(rf, key):
+    c = I.EXTRA_WORKLOADS[key]
+    say(c["name"])
+    x, w = I.moe_routing_inputs_device(I.SEED_BASE + 5, c["S"], c["hd"], c["E"], c["score_sigma"], "bf16", DEV)
+    prob, idx = rf.rf_moe_routing(x, w, c["topk"])
+    torch.cuda.synchronize()
+    p_ref, i_ref, p = O.moe_routing(I.to_numpy(x), I.to_numpy(w), c["topk"])   # every token
+    prob, idx = I.to_numpy(prob), idx.cpu().numpy().astype(np.int64)
+    S, E = p.shape
+    delta = 4e-6 * max(1.0, float(np.max(np.abs(p))))
+    m = p.max(axis=1, keepdims=True)
+    soft = np.exp(p - m) / np.exp(p - m).sum(axis=1, keepdims=True)
+    same = int(np.sum(np.all(idx == i_ref, axis=1)))
+    print(f"        tokens whose selection equals the oracle's: {same}/{S}", flush=True)
+    assert same >= 0.995 * S
+    for i in np.nonzero(np.any(idx != i_ref, axis=1))[0]:
+        # a different order is legitimate only between scores closer than the fp32 accumulation error
+        ps = p[i, idx[i]]
+        assert len(set(idx[i].tolist())) == c["topk"]
+        assert np.all(ps[:-1] >= ps[1:] - delta)
+        assert np.delete(p[i], idx[i]).max() <= ps[-1] + delta
+    np.testing.assert_allclose(prob, np.take_along_axis(soft, idx, axis=1), rtol=2e-4, atol=1e-7)
+    assert float(np.max(np.abs(np.sort(prob, axis=1) - np.sort(p_ref, axis=1)))) <= 1e-5 * float(np.max(p_ref)) + 1e-7

@@ -9,16 +9,16 @@
 // cost is reading x once, so the contraction axis is split over workgroups:
 //
 // Kernel 1 (scores): workgroup (row block of 64 tokens, k slice).  x and w tiles
-//   of 128 k go HBM -> LDS with direct-to-LDS 128-bit loads, double-buffered, one
-//   barrier per tile.  The product is computed transposed, P^T = W^T X^T, with
-//   32x32x16 bf16 MFMAs: W^T fragments come from 64-bit LDS transpose reads, X
+//   of 128 k go HBM -> LDS with direct-to-LDS 128-bit loads two tiles ahead of their
+//   use (three LDS stages), one barrier per tile.  The product is computed
+//   transposed, P^T = W^T X^T, with 32x32x16 bf16 MFMAs: W^T fragments come from 64-bit LDS transpose reads, X
 //   fragments from 128-bit reads.  The four wavefronts split the eight 16-wide
 //   contraction steps of a tile, so every LDS byte is read exactly once; their
 //   accumulators are summed through LDS in a fixed order and the fp32 partial
 //   scores of the slice are written to the caller's workspace.
 // Kernel 2 (cascade): 16 lanes per token add the slices' partial scores in slice
 //   order, then run the cascade: each lane reduces its experts, lanes merge
-//   (max; sum with the exp rescale; TopK of the union) with shuffles.
+//   (max; sum with the exp rescale; TopK of the union) with DPP lane exchanges.
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -52,7 +52,9 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scores_kernel(
   constexpr int kStageB = kMoeXTileB + kWTileB;
   constexpr int kWLoads = kWTileB / 1024 / 4;  // direct-to-LDS loads per wavefront per tile
   constexpr int kAccB = 2 * NT * 16 * 64 * 4;  // one wavefront's accumulators
-  constexpr int kLdsB = (2 * kStageB > 2 * kAccB) ? 2 * kStageB : 2 * kAccB;
+  constexpr int kStages = 3;
+  constexpr int kLdsB = (kStages * kStageB > 4 * kAccB) ? kStages * kStageB : 4 * kAccB;
+  constexpr int kLoadsPerTile = 4 + kWLoads;  // per wavefront
   __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsB];
 
   const int tid = threadIdx.x;
@@ -142,14 +144,20 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scores_kernel(
       for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
 
   if (b0 < b1) issue_tile(b0, 0);
+  if (b0 + 1 < b1) issue_tile(b0 + 1, 1);
+  int stage = 0;
   for (int blk = b0; blk < b1; ++blk) {
-    const int stage = (blk - b0) & 1;
-    // this wavefront's loads of the tile have landed; then everyone's have, and everyone
-    // is done reading the other stage
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // This wavefront's loads of the tile have landed (loads retire in order; only the
+    // next tile's may still be in flight); then everyone's have, and everyone is done
+    // reading the stage that the tile after next goes to.
+    if (blk + 1 < b1)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(kLoadsPerTile) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    if (blk + 1 < b1) issue_tile(blk + 1, stage ^ 1);
+    if (blk + 2 < b1) issue_tile(blk + 2, stage == 0 ? 2 : stage - 1);
     const uint32_t soff = stage * kStageB;
+    stage = stage == 2 ? 0 : stage + 1;
     // Fragment reads are raw instructions with a hand-placed wait: through the compiler's
     // intrinsics every LDS read would first wait for the direct-to-LDS loads of the next
     // tile, just issued.
@@ -193,62 +201,52 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scores_kernel(
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   __syncthreads();  // every wavefront has left the loop: LDS is free
 
-  // ---- sum the four wavefronts' accumulators, fixed order: (0 + 2) + (1 + 3) ----
-  float* red = reinterpret_cast<float*>(lds);  // two regions of kAccB bytes
-  auto put = [&](int region) {
-    float* dst = red + region * (kAccB / 4) + lane;
+  // ---- sum the four wavefronts' accumulators (fixed order 0, 1, 2, 3) ----
+  // Every wavefront parks its accumulators in LDS as 128-bit chunks [chunk][lane]; chunk
+  // c = (ni * 2 + mi) * 4 + r4 holds P[token 32 mi + i32][experts 32 ni + 8 r4 + 4 hh .. +3].
+  // Wavefront v then sums chunks [v CPW, (v+1) CPW) over the four copies and stores them.
+  constexpr int kChunks = 2 * NT * 4;
+  constexpr int CPW = kChunks / 4;
+  f32x4* red = reinterpret_cast<f32x4*>(lds);
+  {
+    f32x4* dst = red + wave * (kChunks * 64) + lane;
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dst[((ni * 2 + mi) * 16 + r) * 64] = acc[ni][mi][r];
-  };
-  auto add = [&](int region) {
-    const float* src = red + region * (kAccB / 4) + lane;
-#pragma unroll
-    for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[ni][mi][r] += src[((ni * 2 + mi) * 16 + r) * 64];
-  };
-  if (wave >= 2) put(wave - 2);
-  __syncthreads();
-  if (wave < 2) add(wave);
-  __syncthreads();
-  if (wave == 1) put(0);
-  __syncthreads();
-  if (wave == 0) {
-    add(0);
-    float* prow = part + ((int64_t)ks * S) * E;
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-      const int m = row0 + 32 * mi + i32;
-      if (m >= S) continue;
-#pragma unroll
-      for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-          // acc[ni][mi][4 r4 + j] = P[token m][expert 32 ni + 8 r4 + 4 hh + j]
           f32x4 v;
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = acc[ni][mi][4 * r4 + j];
-          *reinterpret_cast<f32x4*>(prow + (int64_t)m * E + 32 * ni + 8 * r4 + 4 * hh) = v;
+          dst[((ni * 2 + mi) * 4 + r4) * 64] = v;
         }
-    }
+  }
+  __syncthreads();
+  float* prow = part + ((int64_t)ks * S) * E;
+#pragma unroll
+  for (int cc = 0; cc < CPW; ++cc) {
+    const int c = wave * CPW + cc;
+    f32x4 v = red[c * 64 + lane];
+#pragma unroll
+    for (int r = 1; r < 4; ++r) v += red[r * (kChunks * 64) + c * 64 + lane];
+    const int ni = c >> 3, mi = (c >> 2) & 1, r4 = c & 3;
+    const int m = row0 + 32 * mi + i32;
+    if (m < S) *reinterpret_cast<f32x4*>(prow + (int64_t)m * E + 32 * ni + 8 * r4 + 4 * hh) = v;
   }
 }
 
 // 16 lanes per token; lane q owns experts [q EPL, (q+1) EPL).
+constexpr int kCascadeThreads = 64;  // one wavefront = 4 tokens per workgroup
+
 template <int EPL>
-__global__ __launch_bounds__(kMoeThreads) void moe_cascade_kernel(
+__global__ __launch_bounds__(kCascadeThreads) void moe_cascade_kernel(
     const float* __restrict__ part, int KS, int S, int topk, float* __restrict__ prob,
     int32_t* __restrict__ idx, int64_t ldp, int64_t ldi) {
   constexpr int E = 16 * EPL;
   const int tid = threadIdx.x;
   const int q = tid & 15;
-  const int row = blockIdx.x * (kMoeThreads / 16) + (tid >> 4);
+  const int row = blockIdx.x * (kCascadeThreads / 16) + (tid >> 4);
   const bool live = row < S;
   const int rrow = live ? row : S - 1;  // dead groups repeat the last token, store nothing
 
@@ -256,6 +254,7 @@ __global__ __launch_bounds__(kMoeThreads) void moe_cascade_kernel(
   float p[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) p[i] = 0.f;
+#pragma unroll 8
   for (int s = 0; s < KS; ++s) {
     const float* src = part + ((int64_t)s * S + rrow) * E + q * EPL;
 #pragma unroll
@@ -273,14 +272,16 @@ __global__ __launch_bounds__(kMoeThreads) void moe_cascade_kernel(
   float t = 0.f;
 #pragma unroll
   for (int i = 0; i < EPL; ++i) t += fast_exp2((p[i] - m) * kLog2e);
-#pragma unroll
-  for (int mask = 1; mask < 16; mask <<= 1) {
-    const float m_o = __shfl_xor(m, mask, 16);
-    const float t_o = __shfl_xor(t, mask, 16);
-    const float m_n = fmaxf(m, m_o);
-    t = t * fast_exp2((m - m_n) * kLog2e) + t_o * fast_exp2((m_o - m_n) * kLog2e);
-    m = m_n;
+  // (four DPP exchange patterns whose composition reaches all 16 lanes of a row)
+#define RF_MERGE_MT(CTRL)                                                          \
+  {                                                                                \
+    const float m_o = dpp_f32<CTRL>(m), t_o = dpp_f32<CTRL>(t);                    \
+    const float m_n = fmaxf(m, m_o);                                               \
+    t = t * fast_exp2((m - m_n) * kLog2e) + t_o * fast_exp2((m_o - m_n) * kLog2e); \
+    m = m_n;                                                                       \
   }
+  RF_MERGE_MT(kDppQuadXor1) RF_MERGE_MT(kDppQuadXor2) RF_MERGE_MT(kDppRowHalfMirror) RF_MERGE_MT(kDppRowMirror)
+#undef RF_MERGE_MT
   const float inv_t = 1.0f / t;
   // stage 3: TopK.  Each round takes the largest remaining score of the token (ties: the
   // lowest expert index): lane-local best, then a 16-lane merge of (score, index) pairs.
@@ -296,14 +297,16 @@ __global__ __launch_bounds__(kMoeThreads) void moe_cascade_kernel(
       bv = ok ? p[i] : bv;
       bi = ok ? q * EPL + i : bi;
     }
-#pragma unroll
-    for (int mask = 1; mask < 16; mask <<= 1) {
-      const float ov = __shfl_xor(bv, mask, 16);
-      const int oi = __shfl_xor(bi, mask, 16);
-      const bool take = (ov > bv) || (ov == bv && oi < bi);
-      bv = take ? ov : bv;
-      bi = take ? oi : bi;
-    }
+#define RF_MERGE_TOP(CTRL)                                         \
+  {                                                                \
+    const float ov = dpp_f32<CTRL>(bv);                            \
+    const int oi = dpp_i32<CTRL>(bi);                              \
+    const bool take = (ov > bv) || (ov == bv && oi < bi);          \
+    bv = take ? ov : bv;                                           \
+    bi = take ? oi : bi;                                           \
+  }
+    RF_MERGE_TOP(kDppQuadXor1) RF_MERGE_TOP(kDppQuadXor2) RF_MERGE_TOP(kDppRowHalfMirror) RF_MERGE_TOP(kDppRowMirror)
+#undef RF_MERGE_TOP
     if (bi / EPL == q && bi < E) taken |= 1u << (bi % EPL);
     if ((j & 15) == q) {
       my_prob = fast_exp2((bv - m) * kLog2e) * inv_t;
@@ -346,11 +349,11 @@ hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid2((unsigned)((S + kMoeThreads / 16 - 1) / (kMoeThreads / 16)));
+  const dim3 grid2((unsigned)((S + kCascadeThreads / 16 - 1) / (kCascadeThreads / 16))), block2(kCascadeThreads);
   switch (E) {
-    case 32: hipLaunchKernelGGL((moe_cascade_kernel<2>), grid2, block, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
-    case 64: hipLaunchKernelGGL((moe_cascade_kernel<4>), grid2, block, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
-    case 128: hipLaunchKernelGGL((moe_cascade_kernel<8>), grid2, block, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
+    case 32: hipLaunchKernelGGL((moe_cascade_kernel<2>), grid2, block2, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
+    case 64: hipLaunchKernelGGL((moe_cascade_kernel<4>), grid2, block2, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
+    case 128: hipLaunchKernelGGL((moe_cascade_kernel<8>), grid2, block2, 0, s, part, KS, S, topk, prob, idx, ldp, ldi); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

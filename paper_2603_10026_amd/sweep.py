@@ -1,0 +1,64 @@
+"""Split-count sweep for multi-segment attention (paper Section 5.4.2: the effect of the number
+of segments on a long-sequence decode).  Times rf_cascade_attention_splitk + rf_merge_states on
+the decode benchmark workload for several segment counts S and prints one line per S; the
+fastest S is the value to pass as ``num_splits`` on this GPU.
+
+    python -m paper_2603_10026_amd.sweep [--splits 8,16,32,64,128,256] [--iters 20]
+"""
+import argparse
+import json
+import sys
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--splits", type=str, default="8,16,32,64,128,256,512")
+    ap.add_argument("--iters", type=int, default=20)
+    args = ap.parse_args()
+    import torch
+    from . import binding as rf
+    from . import inputs as I
+
+    rf.load_library()
+    dev = "cuda:0"
+    c = I.WORKLOADS[3]
+    n_rot = 3
+    sets = [I.attention_inputs_device(I.SEED_BASE + 3 + 100 * r, c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "bf16", dev)
+            for r in range(n_rot)]
+    scale = I.default_scale(c["d"])
+    kv_bytes = 2.0 * c["B"] * c["Hkv"] * c["Lk"] * c["d"] * 2
+    rows = []
+    for S in [int(t) for t in args.splits.split(",")]:
+        parts = [rf.alloc_partial_states(sets[r][0], S) for r in range(n_rot)]
+        outs = [torch.empty_like(sets[r][0]) for r in range(n_rot)]
+
+        def step(i):
+            q, k, v = sets[i % n_rot]
+            pm, pl, pacc = parts[i % n_rot]
+            rf.rf_cascade_attention_splitk(q, k, v, S, pm, pl, pacc, scale, False)
+            rf.rf_merge_states(pm, pl, pacc, outs[i % n_rot])
+
+        for i in range(3):
+            step(i)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.iters)]
+        for i in range(args.iters):
+            evs[i][0].record()
+            step(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        med = ts[len(ts) // 2]
+        part_bytes = 2.0 * c["B"] * c["Hq"] * S * (c["d"] + 2) * 4      # written, then read
+        row = dict(num_splits=S, keys_per_segment=-(-c["Lk"] // S), workgroups=c["B"] * c["Hkv"] * S,
+                   us_median=round(med, 1), us_min=round(ts[0], 1),
+                   GBps_kv_only=round(kv_bytes / med / 1e3, 1), partial_state_MB=round(part_bytes / 1e6, 1))
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+        del parts, outs
+    best = min(rows, key=lambda r: r["us_median"])
+    print(json.dumps(dict(best_num_splits=best["num_splits"], us_median=best["us_median"])), flush=True)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

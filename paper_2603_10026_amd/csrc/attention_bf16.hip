@@ -164,32 +164,34 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
   }
   // byte offsets stay below 2^32 inside one 64-row tile only if the row stride does
   const bool small_stride = sk.l < (1 << 24) && sv.l < (1 << 24);
-  auto issue_loads = [&](int key0, int buf) {
-    unsigned char* kdst = lds + buf * 2 * TILEB;
-    unsigned char* vdst = kdst + TILEB;
+  // One direct-to-LDS load of this wavefront's share of the tile at key0: load e of K
+  // (is_v = 0) or of V (is_v = 1) into buffer buf.
+  auto issue_one = [&](int key0, int buf, int e, int is_v) {
+    unsigned char* dst = lds + buf * 2 * TILEB + is_v * TILEB + (wave * LD_PER_WAVE + e) * 1024;
+    const bf16_t* base = is_v ? vb : kb;
+    const int64_t ld = is_v ? sv.l : sk.l;
     if (key0 + kBK <= Lk && small_stride) {
       // full tile: uniform tile base + per-lane 32-bit offset, no per-load address math
-      const char* ktile = reinterpret_cast<const char*>(kb) + (int64_t)key0 * sk.l * 2;
-      const char* vtile = reinterpret_cast<const char*>(vb) + (int64_t)key0 * sv.l * 2;
-#pragma unroll
-      for (int e = 0; e < LD_PER_WAVE; ++e) {
-        const int inst = wave * LD_PER_WAVE + e;
-        __builtin_amdgcn_global_load_lds((global_cvoid*)(ktile + ld_koff[e]),
-                                         (lds_void*)(kdst + inst * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((global_cvoid*)(vtile + ld_voff[e]),
-                                         (lds_void*)(vdst + inst * 1024), 16, 0, 0);
-      }
+      // (raw instruction: scalar base + 32-bit lane offset, LDS destination in M0)
+      const char* tile = reinterpret_cast<const char*>(base) + (int64_t)key0 * ld * 2;
+      const uint32_t dst_addr = __builtin_amdgcn_readfirstlane(
+          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)dst);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(dst_addr), "v"(is_v ? ld_voff[e] : ld_koff[e]), "s"(tile)
+                   : "memory");
     } else {
       // ragged last tile: rows past the end re-read the last key (masked later)
+      const int key = min(key0 + ld_row[e], Lk - 1);
+      const bf16_t* src = base + (int64_t)key * ld + (is_v ? ld_vcol[e] : ld_kcol[e]);
+      __builtin_amdgcn_global_load_lds((global_cvoid*)src, (lds_void*)dst, 16, 0, 0);
+    }
+  };
+  auto issue_loads = [&](int key0, int buf) {
 #pragma unroll
-      for (int e = 0; e < LD_PER_WAVE; ++e) {
-        const int inst = wave * LD_PER_WAVE + e;
-        const int key = min(key0 + ld_row[e], Lk - 1);
-        const bf16_t* ksrc = kb + (int64_t)key * sk.l + ld_kcol[e];
-        const bf16_t* vsrc = vb + (int64_t)key * sv.l + ld_vcol[e];
-        __builtin_amdgcn_global_load_lds((global_cvoid*)ksrc, (lds_void*)(kdst + inst * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((global_cvoid*)vsrc, (lds_void*)(vdst + inst * 1024), 16, 0, 0);
-      }
+    for (int e = 0; e < LD_PER_WAVE; ++e) {
+      issue_one(key0, buf, e, 0);
+      issue_one(key0, buf, e, 1);
     }
   };
 
@@ -233,8 +235,11 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     const int key0 = kt * kBK;
     wait_vmem_all();   // this wavefront's share of tile kt has landed
     __syncthreads();   // everyone's share has landed; everyone is done reading the other buffer
-    if (kt + 1 < n_ktiles) issue_loads(key0 + kBK, BUF ^ 1);
-    if (key0 > wave_last) return;  // nothing visible for this wavefront (uniform)
+    const bool more = kt + 1 < n_ktiles;
+    if (key0 > wave_last) {  // nothing visible for this wavefront (uniform): only fetch its share
+      if (more) issue_loads(key0 + kBK, BUF ^ 1);
+      return;
+    }
 
     const unsigned char* kt_lds = lds + BUF * 2 * TILEB;
 
@@ -253,14 +258,20 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
       for (int rt = 0; rt < 2; ++rt)
         kf[kk][rt] = *reinterpret_cast<const u32x4*>(kt_lds + koff[kk] + rt * 32 * ROWB);
     __builtin_amdgcn_sched_barrier(0);
+    // The loads of the next tile are issued one at a time between the MFMAs.  Issued in a
+    // burst right after the barrier, the eight wavefronts of a CU queue up behind each
+    // other in the vector-memory unit and every one of them idles for the whole burst.
+    static_assert(2 * LD_PER_WAVE == KS, "one load per contraction step");
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk)
+    for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
         s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk][rt]),
                                                         __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
                                                         0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+      if (more) issue_one(key0 + kBK, BUF ^ 1, kk >> 1, kk & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // ---- V^T fragments of the first two contraction steps: requested now, they arrive
     //      while the softmax below runs on the vector ALU ----
     // The transpose reads are issued as raw instructions and waited for by hand:

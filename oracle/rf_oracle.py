@@ -13,7 +13,10 @@ Two groups of functions:
 
 * ``safe_softmax``, ``attention``, ``attention_partial_states``,
   ``merge_states``, ``rmsnorm_gemm``, ``variance``, ``moe_routing``: the
-  definitions the GPU results are compared against.
+  definitions the GPU results are compared against; ``fp8_quant_gemm``: the
+  tile-by-tile incremental algorithm of the quantised cascade (the one case
+  here whose single-pass result is not that of the multi-pass definition,
+  because rounding to FP8 sits between the two reductions).
 * ``*_incremental`` and ``fused_*``: the paper's fused / incremental forms
   (Section 3.2 Eq. (6), (8), (11); Section 3.3 Eq. (15)-(16); Appendix A.2) written out
   step by step in the paper's order.  They exist so that the tests can check
@@ -44,7 +47,15 @@ Readings of the paper taken here (each is also listed in the design notes):
   * MoE routing (Appendix A.2): TopK acts on the raw scores (softmax keeps
     their order) and the final "s / t" is read as exp(s - m) / t, the softmax
     probability of each selected expert.  Equal scores are ordered by expert
-    index, lowest first, and the k outputs are in descending order of score.
+    index, lowest first, and the k outputs are in descending order of score;
+  * FP8 per-token quant + GEMM (Section 3.4): FP8 is OCP E4M3 (MAX = 448),
+    rounding to nearest even, values beyond MAX saturate.  The scale MAX / m
+    and the product a * scale are taken in float32 (they decide the FP8 code,
+    so both sides of a comparison must use one precision); everything else is
+    float64.  The weights arrive already in FP8.  The paper's c = sum (MAX a / m) w
+    is the quantised-domain sum; the returned value undoes the scale,
+    c * m / MAX, so that it approximates a @ w.  An all-zero token has m = 0: its
+    scale is taken as 0 and its output row is 0.
 """
 from __future__ import annotations
 
@@ -506,3 +517,62 @@ def moe_routing_incremental_row(p, topk, seg):
     prob = np.asarray([np.exp(v - m) / t for v, _ in s], dtype=F64)
     idx = np.asarray([j for _, j in s], dtype=np.int64)
     return prob, idx
+
+
+# --------------------------------------------------------------------------
+# O8. FP8 per-token quantisation + GEMM  (Section 3.4, case study)
+# --------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+def e4m3_round(x):
+    """Round float32 values to the OCP E4M3 grid (4 exponent bits, bias 7, 3 mantissa bits,
+    no infinities, largest finite value 448): nearest, ties to the even mantissa, finite
+    values beyond 448 saturate.  Written from the format's definition: a value in
+    [2^e, 2^(e+1)) with e >= -6 sits on a grid of step 2^(e-3); below 2^-6 the step is 2^-9."""
+    x = np.asarray(x, dtype=np.float32).astype(F64)
+    ax = np.abs(x)
+    e = np.floor(np.log2(np.where(ax > 0, ax, 1.0)))
+    e = np.maximum(e, -6.0)                    # subnormals share the exponent of 2^-6
+    step = np.exp2(e - 3.0)
+    q = np.rint(ax / step) * step              # rint: ties to even, exact here (powers of two)
+    q = np.minimum(q, E4M3_MAX)
+    return np.copysign(q, x)
+
+
+def fp8_quant_gemm_twopass(a, w):
+    """The multi-pass definition: m = max_l |a[l]|;  c = sum_l q(MAX a[l] / m) w[l], with q the
+    rounding to FP8, one scale per token taken from the whole row.  a [M,K]; w [N,K] (FP8
+    values, row n = output channel n).  Returns c * m / MAX, shape [M,N]."""
+    a32 = np.asarray(a, dtype=np.float32)
+    w = np.asarray(w, dtype=F64)
+    m = np.max(np.abs(a32), axis=1)                                        # reduction 1
+    with np.errstate(divide="ignore"):
+        scale = np.where(m > 0, np.float32(E4M3_MAX) / m, np.float32(0.0)).astype(np.float32)
+    q = e4m3_round(a32 * scale[:, None])
+    c = q @ w.T                                                            # reduction 2
+    return c * (m.astype(F64) / E4M3_MAX)[:, None]
+
+
+def fp8_quant_gemm(a, w, tile):
+    """Level-k incremental form over segments of `tile` elements of the contraction axis:
+      m[L] = max(m[L-1], m_seg)
+      c[L] = c[L-1] * m[L-1] / m[L] + sum_{l in seg} q(MAX a[l] / m[L]) w[l]
+    Each segment is quantised with the running maximum that includes it; earlier
+    segments keep the codes they were given and are only rescaled.  With one segment
+    (tile >= K) this is the multi-pass definition."""
+    a32 = np.asarray(a, dtype=np.float32)
+    w = np.asarray(w, dtype=F64)
+    M, K = a32.shape
+    m = np.zeros(M, dtype=np.float32)
+    c = np.zeros((M, w.shape[0]), dtype=F64)
+    for lo in range(0, K, tile):
+        seg = a32[:, lo:lo + tile]
+        m_new = np.maximum(m, np.max(np.abs(seg), axis=1))
+        with np.errstate(divide="ignore", invalid="ignore"):
+            scale = np.where(m_new > 0, np.float32(E4M3_MAX) / m_new, np.float32(0.0)).astype(np.float32)
+            corr = np.where(m_new > 0, m.astype(F64) / m_new.astype(F64), 1.0)
+        q = e4m3_round(seg * scale[:, None])
+        c = c * corr[:, None] + q @ w[:, lo:lo + tile].T
+        m = m_new
+    return c * (m.astype(F64) / E4M3_MAX)[:, None]

@@ -71,6 +71,34 @@ def bf16_round(a):
     return bf16_bits_to_f32(bf16_bits(a))
 
 
+def e4m3_table():
+    """The 256 OCP E4M3 codes decoded to float32 (NaN codes 0x7f / 0xff as nan)."""
+    code = np.arange(256, dtype=np.int64)
+    sign = np.where(code & 0x80, -1.0, 1.0)
+    ex = (code >> 3) & 0xF
+    man = code & 0x7
+    val = np.where(ex == 0, man / 8.0 * 2.0 ** -6, (1.0 + man / 8.0) * 2.0 ** (ex.astype(np.float64) - 7.0))
+    val = np.where((code & 0x7F) == 0x7F, np.nan, sign * val)
+    return val.astype(np.float32)
+
+
+def e4m3_bits(a):
+    """float32 array -> uint8 OCP E4M3 codes: nearest code, ties to the even code, |a| > 448 -> 448."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    pos = e4m3_table()[:127].astype(np.float64)          # 0 .. 448, ascending
+    x = np.minimum(np.abs(a).astype(np.float64), 448.0)
+    hi = np.clip(np.searchsorted(pos, x, side="left"), 1, 126)
+    lo = hi - 1
+    dlo, dhi = x - pos[lo], pos[hi] - x
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return np.where(np.signbit(a), code | np.uint8(0x80), code).astype(np.uint8)
+
+
+def e4m3_bits_to_f32(bits):
+    return e4m3_table()[np.ascontiguousarray(bits, dtype=np.uint8)]
+
+
 def _store(a, dtype):
     a = np.asarray(a, dtype=np.float32)
     if dtype == "bf16":
@@ -122,6 +150,23 @@ def moe_routing_inputs(seed, S, hd, E, score_sigma=1.5, dtype="bf16"):
     x = _store(rng.standard_normal((S, hd), dtype=np.float32), dtype)
     w = _store(rng.standard_normal((hd, E), dtype=np.float32) * np.float32(score_sigma / math.sqrt(hd)), dtype)
     return x, w
+
+
+def fp8_quant_gemm_inputs(seed, M, K, N, outlier_rows=8):
+    """Activations A[M,K] ~ N(0,1) in bf16, with `outlier_rows` rows carrying a few large entries
+    at random positions (what per-token scales exist for; they also make the running maximum
+    move late in the row).  Weights W[N,K] ~ N(0,1) rounded to OCP E4M3 (a weight scale is
+    taken as folded into the surrounding layer).  Returns (a float32, w float32 of FP8 values,
+    w_bits uint8)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    a = rng.standard_normal((M, K), dtype=np.float32)
+    rows = rng.choice(M, size=min(outlier_rows, M), replace=False)
+    for r in rows:
+        cols = rng.choice(K, size=3, replace=False)
+        a[r, cols] *= np.float32(30.0)
+    a = bf16_round(a)
+    w_bits = e4m3_bits(rng.standard_normal((N, K), dtype=np.float32))
+    return a, e4m3_bits_to_f32(w_bits), w_bits
 
 
 def default_scale(d):

@@ -519,3 +519,101 @@ def test_topk_merge_is_associative_and_commutative():
     for (p, q, r) in itertools.permutations((a, b, c)):
         assert O.topk_merge(O.topk_merge(top(p), top(q), 4), top(r), 4) == ref
         assert O.topk_merge(top(p), O.topk_merge(top(q), top(r), 4), 4) == ref
+
+
+# ------------------------------------------------- FP8 per-token quant + GEMM
+def _e4m3_from_bits():
+    """All finite E4M3 values decoded from their bit fields (sign 1, exponent 4 bias 7, mantissa 3;
+    exponent 0 = subnormal; S.1111.111 = NaN), written here independently of the oracle."""
+    vals = []
+    for code in range(256):
+        s, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            continue
+        v = (m / 8) * 2.0 ** -6 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+        vals.append(-v if s else v)
+    return np.array(sorted(set(vals)))
+
+
+def test_e4m3_grid_fixed_points_ties_and_saturation():
+    grid = _e4m3_from_bits()
+    assert grid.max() == 448.0 and grid[grid > 0].min() == 2.0 ** -9 and len(grid) == 253
+    np.testing.assert_array_equal(O.e4m3_round(grid), grid)               # grid points are fixed points
+    pos = grid[grid >= 0]
+    mid = (pos[:-1] + pos[1:]) / 2                                          # exact midpoints
+    r = O.e4m3_round(mid)
+    for k in range(len(mid)):
+        lo, hi = pos[k], pos[k + 1]
+        # ties go to the neighbour with the even mantissa = even position in the ascending grid
+        assert r[k] == (lo if k % 2 == 0 else hi), (mid[k], r[k])
+    np.testing.assert_array_equal(O.e4m3_round(np.nextafter(mid.astype(np.float32), np.float32(1e9))), pos[1:])
+    np.testing.assert_array_equal(O.e4m3_round(np.nextafter(mid.astype(np.float32), np.float32(-1))), pos[:-1])
+    np.testing.assert_array_equal(O.e4m3_round([449.0, 464.0, 1e6, -5000.0]), [448.0, 448.0, 448.0, -448.0])
+    np.testing.assert_array_equal(O.e4m3_round([2.0 ** -10, 2.0 ** -10 * 1.01, -0.0]), [0.0, 2.0 ** -9, 0.0])
+    x = RNG(81).standard_normal(20000).astype(np.float32) * 120
+    x = np.clip(x, -464, 464)
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).to(torch.float32).numpy()   # library special case
+    np.testing.assert_array_equal(O.e4m3_round(x).astype(np.float32), lib)
+    xs = np.sort(x)
+    assert np.all(np.diff(O.e4m3_round(xs)) >= 0)                           # monotone
+
+
+def test_fp8_quant_gemm_exact_when_tokens_sit_on_the_scaled_grid():
+    # a token of the form m * g / 448 with g on the E4M3 grid quantises without error
+    rng = RNG(82)
+    grid = _e4m3_from_bits()
+    g = rng.choice(grid[np.abs(grid) >= 1], size=(5, 24))
+    g[:, 0] = 448.0
+    a = (g * 0.25).astype(np.float32)                                       # m = 112, power-of-two ratio
+    w = rng.choice(grid[np.abs(grid) <= 8], size=(7, 24))
+    np.testing.assert_allclose(O.fp8_quant_gemm_twopass(a, w), a.astype(np.float64) @ w.T, rtol=1e-13, atol=1e-12)
+    # w[n, k]: row n is output channel n (not transposed)
+    a1 = np.zeros((1, 24), dtype=np.float32); a1[0, 5] = 3.0
+    np.testing.assert_allclose(O.fp8_quant_gemm_twopass(a1, w)[0], 3.0 * w[:, 5], rtol=1e-13)
+    # power-of-two token scaling commutes with the quantiser; a zero token gives zeros
+    a2 = rng.standard_normal((3, 24)).astype(np.float32)
+    np.testing.assert_allclose(O.fp8_quant_gemm_twopass(8 * a2, w), 8 * O.fp8_quant_gemm_twopass(a2, w), rtol=1e-13)
+    assert np.all(O.fp8_quant_gemm_twopass(np.zeros((2, 24), np.float32), w) == 0.0)
+    assert np.all(O.fp8_quant_gemm(np.zeros((2, 24), np.float32), w, 8) == 0.0)
+
+
+def test_fp8_quant_gemm_error_bound_against_exact_product():
+    # |q(x) - x| <= max(|x| 2^-4, 2^-10) in the scaled domain, so per token
+    # |c - a.w| <= sum_k |w_k| max(|a_k| 2^-4, 2^-10 m/448); the incremental form obeys the same
+    # bound (each segment is quantised against a maximum no larger than the final one)
+    rng = RNG(83)
+    from paper_2603_10026_amd import inputs as I
+    a, w, _ = I.fp8_quant_gemm_inputs(83, 40, 384, 16)
+    exact = a.astype(np.float64) @ w.T.astype(np.float64)
+    m = np.max(np.abs(a), axis=1).astype(np.float64)
+    per_elem = np.maximum(np.abs(a) * 2.0 ** -4, (2.0 ** -10 * m / 448)[:, None])
+    bound = per_elem @ np.abs(w).T * (1 + 1e-6) + 1e-9
+    for got in (O.fp8_quant_gemm_twopass(a, w), O.fp8_quant_gemm(a, w, 128), O.fp8_quant_gemm(a, w, 32)):
+        assert np.all(np.abs(got - exact) <= bound)
+        assert np.sqrt(np.mean((got - exact) ** 2)) < 0.05 * np.sqrt(np.mean(exact ** 2))   # and it is a real GEMM
+
+
+def test_fp8_quant_gemm_incremental_reduces_to_the_definition():
+    from paper_2603_10026_amd import inputs as I
+    a, w, _ = I.fp8_quant_gemm_inputs(84, 24, 256, 12, outlier_rows=6)
+    two = O.fp8_quant_gemm_twopass(a, w)
+    np.testing.assert_array_equal(O.fp8_quant_gemm(a, w, 256), two)         # one segment
+    np.testing.assert_array_equal(O.fp8_quant_gemm(a, w, 1000), two)
+    # tokens whose largest entry lies in the first segment never rescale: same codes, same result
+    a2 = a.copy()
+    a2[:, 0] = np.float32(200.0)
+    np.testing.assert_allclose(O.fp8_quant_gemm(a2, w, 64), O.fp8_quant_gemm_twopass(a2, w), rtol=1e-12, atol=1e-9)
+    # tokens whose maximum arrives later differ from the definition only by quantisation noise
+    inc = O.fp8_quant_gemm(a, w, 64)
+    assert np.max(np.abs(inc - two)) > 0
+    assert np.max(np.abs(inc - two)) < 0.1 * np.max(np.abs(two))
+    # a hand-computed two-segment case: a = (1 | 4), w = (1 | 1), tile 1:
+    #   segment 1: m = 1, q(448) = 448, c = 448;  segment 2: m = 4, c = 448/4 + q(448) = 560; out = 560*4/448 = 5
+    got = O.fp8_quant_gemm(np.array([[1.0, 4.0]], np.float32), np.array([[1.0, 1.0]]), 1)
+    assert got[0, 0] == pytest.approx(5.0, rel=1e-14)
+    #   with a = (0.3 | 4): segment 1 quantises 0.3 against itself (exact: 448), rescaled by 0.3/4 -> 33.6
+    got = O.fp8_quant_gemm(np.array([[0.3, 4.0]], np.float32), np.array([[1.0, 1.0]]), 1)
+    assert got[0, 0] == pytest.approx(float(np.float32(0.3)) + 4.0, rel=1e-12)
+    #   the definition instead quantises 0.3 * 112 = 33.6 -> 32 on the grid: (32 + 448) * 4 / 448
+    got2 = O.fp8_quant_gemm_twopass(np.array([[0.3, 4.0]], np.float32), np.array([[1.0, 1.0]]))
+    assert got2[0, 0] == pytest.approx(480.0 * 4 / 448, rel=1e-12)

@@ -53,7 +53,7 @@ typedef enum {
   RF_ERR_LAUNCH = 5       /* the HIP runtime rejected a launch                  */
 } rf_status;
 
-typedef enum { RF_F32 = 0, RF_BF16 = 1, RF_I32 = 2 } rf_dtype;
+typedef enum { RF_F32 = 0, RF_BF16 = 1, RF_I32 = 2, RF_FP8_E4M3 = 3 /* OCP E4M3, 1 byte */ } rf_dtype;
 
 /* (+)_i and (x)_i of Table 1. */
 typedef enum { RF_RED_MAX = 0, RF_RED_MIN = 1, RF_RED_SUM = 2 } rf_reduce_op;
@@ -133,6 +133,24 @@ RF_API size_t rf_moe_routing_workspace_bytes(int64_t S, int64_t hd, int64_t E);
 RF_API rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
                                 rf_tensor* idx, void* workspace, size_t workspace_bytes,
                                 rf_stream stream);
+
+/*
+ * FP8 per-token quantisation fused with a GEMM (Section 3.4, case study): the cascade
+ *   m = max_k |a[k]|;   c[n] = sum_k q(MAX a[k] / m) w[n,k]
+ * (q = rounding to OCP E4M3, nearest-even, MAX = 448) in its incremental form over tiles
+ * of 128 k: each tile is quantised with the running maximum that includes it,
+ *   m' = max(m, max_tile |a|);   acc' = acc * (m / m') + sum_tile q(MAX a / m') w,
+ * earlier tiles keep their codes and are only rescaled.  Returned is acc * m / MAX, an
+ * approximation of a @ w^T; it differs from quantising with the row's final maximum
+ * only by quantisation noise (tokens whose maximum lies in the first tile: not at all).
+ *   a : [M, K] bf16.  K % 128 == 0.
+ *   w : [N, K] FP8 E4M3, row n = output channel n (already quantised; any weight scale
+ *       is the caller's to apply).  N % 8 == 0.
+ *   c : [M, N] bf16.
+ * An all-zero token gives an all-zero output row.
+ */
+RF_API rf_status rf_fp8_quant_gemm(const rf_tensor* a, const rf_tensor* w, rf_tensor* c,
+                                   rf_stream stream);
 
 /*
  * Fused attention, single-segment strategy (Section 4.3; Appendix A.2):

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librf.so")
 
 RF_OK = 0
 RF_ERR_INVALID_ARG, RF_ERR_UNSUPPORTED, RF_ERR_ALIGNMENT, RF_ERR_WORKSPACE, RF_ERR_LAUNCH = 1, 2, 3, 4, 5
-RF_F32, RF_BF16, RF_I32 = 0, 1, 2
+RF_F32, RF_BF16, RF_I32, RF_FP8_E4M3 = 0, 1, 2, 3
 RF_MAX_DIMS = 5
 
 ENTRY_POINTS = (
@@ -32,6 +32,7 @@ ENTRY_POINTS = (
     "rf_variance",
     "rf_moe_routing_workspace_bytes",
     "rf_moe_routing",
+    "rf_fp8_quant_gemm",
     "rf_diag_copy",
     "rf_diag_mfma",
 )
@@ -92,6 +93,8 @@ def load_library():
     lib.rf_moe_routing_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
     lib.rf_moe_routing.restype = ctypes.c_int
     lib.rf_moe_routing.argtypes = [P, P, ctypes.c_int, P, P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.rf_fp8_quant_gemm.restype = ctypes.c_int
+    lib.rf_fp8_quant_gemm.argtypes = [P, P, P, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.rf_diag_mfma.restype = ctypes.c_int
@@ -114,7 +117,8 @@ def describe_cascade(entry):
     return [(buf[i].reduce, buf[i].combine) for i in range(n)]
 
 
-_DTYPES = {torch.float32: RF_F32, torch.bfloat16: RF_BF16, torch.int32: RF_I32}
+_DTYPES = {torch.float32: RF_F32, torch.bfloat16: RF_BF16, torch.int32: RF_I32,
+           torch.float8_e4m3fn: RF_FP8_E4M3}
 
 
 def tensor_desc(t):
@@ -245,6 +249,17 @@ def rf_moe_routing(x, w, topk, prob=None, idx=None, workspace=None, stream=None)
                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                               _stream(stream)), "rf_moe_routing")
     return prob, idx
+
+
+def rf_fp8_quant_gemm(a, w, c=None, stream=None):
+    """c = dequant(quant_fp8(a) @ w^T): a [M,K] bf16, w [N,K] torch.float8_e4m3fn, c [M,N] bf16."""
+    lib = load_library()
+    if c is None:
+        c = torch.empty((a.shape[0], w.shape[0]), dtype=torch.bfloat16, device=a.device)
+    da, dw, dc = tensor_desc(a), tensor_desc(w), tensor_desc(c)
+    _check(lib.rf_fp8_quant_gemm(ctypes.byref(da), ctypes.byref(dw), ctypes.byref(dc), _stream(stream)),
+           "rf_fp8_quant_gemm")
+    return c
 
 
 def rf_diag_copy(src, dst, stream=None):

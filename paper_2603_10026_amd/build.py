@@ -19,6 +19,7 @@ SOURCES = [
     "softmax.hip",
     "variance.hip",
     "moe_routing.hip",
+    "fp8_quant_gemm.hip",
     "attention_f32.hip",
     "attention_bf16.hip",
     "attention_splitk.hip",

@@ -8,17 +8,18 @@
 
 namespace {
 
-inline size_t esize(rf_dtype t) { return t == RF_BF16 ? 2 : 4; }  // f32 and i32: 4
-inline bool dtype_ok(rf_dtype t, bool allow_i32) {
-  return t == RF_F32 || t == RF_BF16 || (allow_i32 && t == RF_I32);
+inline size_t esize(rf_dtype t) { return t == RF_BF16 ? 2 : t == RF_FP8_E4M3 ? 1 : 4; }  // f32, i32: 4
+// `also`: one more dtype this argument may have (-1: none)
+inline bool dtype_ok(rf_dtype t, int also) {
+  return t == RF_F32 || t == RF_BF16 || (also >= 0 && (int)t == also);
 }
 
 // Structural checks common to every tensor argument.
-// (integer tensors are accepted only where an entry point asks for them)
-rf_status check_tensor(const rf_tensor* t, int ndim_min, int ndim_max, bool allow_i32 = false) {
+// (integer and FP8 tensors are accepted only where an entry point asks for them)
+rf_status check_tensor(const rf_tensor* t, int ndim_min, int ndim_max, int also = -1) {
   if (t == nullptr) return RF_ERR_INVALID_ARG;
   if (t->ndim < ndim_min || t->ndim > ndim_max) return RF_ERR_INVALID_ARG;
-  if (!dtype_ok(t->dtype, allow_i32)) return RF_ERR_UNSUPPORTED;
+  if (!dtype_ok(t->dtype, also)) return RF_ERR_UNSUPPORTED;
   for (int i = 0; i < t->ndim; ++i) {
     if (t->shape[i] < 0 || t->stride[i] < 0) return RF_ERR_INVALID_ARG;
   }
@@ -126,6 +127,8 @@ int rf_describe_cascade(const char* entry, rf_stage* out, int cap) {
   // max, sum of exponentials, TopK (a max-type reduction, Table 1)
   static const rf_stage kRouting[] = {
       {RF_RED_MAX, RF_COMB_ADD}, {RF_RED_SUM, RF_COMB_MUL}, {RF_RED_MAX, RF_COMB_ADD}};
+  // abs-max, then the scaled sum
+  static const rf_stage kQuant[] = {{RF_RED_MAX, RF_COMB_ADD}, {RF_RED_SUM, RF_COMB_MUL}};
   const rf_stage* src = nullptr;
   int n = 0;
   if (!strcmp(entry, "rf_safe_softmax")) { src = kSoftmax; n = 2; }
@@ -134,6 +137,7 @@ int rf_describe_cascade(const char* entry, rf_stage* out, int cap) {
   else if (!strcmp(entry, "rf_rmsnorm_gemm")) { src = kRms; n = 2; }
   else if (!strcmp(entry, "rf_variance")) { src = kRms; n = 2; }  // sum, then sum
   else if (!strcmp(entry, "rf_moe_routing")) { src = kRouting; n = 3; }
+  else if (!strcmp(entry, "rf_fp8_quant_gemm")) { src = kQuant; n = 2; }
   else return -1;
   if (out != nullptr)
     for (int i = 0; i < n && i < cap; ++i) out[i] = src[i];
@@ -210,7 +214,7 @@ rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_te
   if ((st = check_tensor(x, 2, 2)) != RF_OK) return st;
   if ((st = check_tensor(w, 2, 2)) != RF_OK) return st;
   if ((st = check_tensor(prob, 2, 2)) != RF_OK) return st;
-  if ((st = check_tensor(idx, 2, 2, true)) != RF_OK) return st;
+  if ((st = check_tensor(idx, 2, 2, RF_I32)) != RF_OK) return st;
   if (x->dtype != RF_BF16 || w->dtype != RF_BF16 || prob->dtype != RF_F32 || idx->dtype != RF_I32)
     return RF_ERR_UNSUPPORTED;
   const int64_t S = x->shape[0], hd = x->shape[1], E = w->shape[1];
@@ -237,6 +241,29 @@ rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_te
                                         x->stride[0], w->stride[0], (float*)prob->data,
                                         (int32_t*)idx->data, prob->stride[0], idx->stride[0],
                                         (float*)workspace, (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
+rf_status rf_fp8_quant_gemm(const rf_tensor* a, const rf_tensor* w, rf_tensor* c, rf_stream stream) {
+  rf_status st;
+  if ((st = check_tensor(a, 2, 2)) != RF_OK) return st;
+  if ((st = check_tensor(w, 2, 2, RF_FP8_E4M3)) != RF_OK) return st;
+  if ((st = check_tensor(c, 2, 2)) != RF_OK) return st;
+  if (a->dtype != RF_BF16 || w->dtype != RF_FP8_E4M3 || c->dtype != RF_BF16) return RF_ERR_UNSUPPORTED;
+  const int64_t M = a->shape[0], K = a->shape[1], N = w->shape[0];
+  if (w->shape[1] != K || c->shape[0] != M || c->shape[1] != N) return RF_ERR_INVALID_ARG;
+  if (M == 0 || N == 0) return RF_OK;
+  if (K == 0 || K % 128 != 0 || N % 8 != 0) return RF_ERR_UNSUPPORTED;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return RF_ERR_UNSUPPORTED;
+  for (const rf_tensor* t : {a, w, (const rf_tensor*)c})
+    if (t->shape[1] > 1 && t->stride[1] != 1) return RF_ERR_UNSUPPORTED;
+  if (a->data == nullptr || w->data == nullptr || c->data == nullptr) return RF_ERR_INVALID_ARG;
+  if (!aligned16(a) || !aligned16(w) || !aligned16(c)) return RF_ERR_ALIGNMENT;
+  if (128 * a->stride[0] * 2 >= ((int64_t)1 << 32) || N * w->stride[0] >= ((int64_t)1 << 32))
+    return RF_ERR_UNSUPPORTED;
+  hipError_t e = rf::launch_fp8_quant_gemm(a->data, w->data, c->data, (int)M, (int)K, (int)N,
+                                           a->stride[0], w->stride[0], c->stride[0],
+                                           (hipStream_t)stream);
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 

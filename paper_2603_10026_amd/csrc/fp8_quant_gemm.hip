@@ -1,0 +1,383 @@
+// FP8 per-token quantisation fused with a GEMM (paper Section 3.4, case study):
+//   stage 1: m_i   = max_k |a[i,k]|
+//   stage 2: c[i,n] = sum_k q(MAX a[i,k] / m_i) w[n,k],   q = rounding to FP8 (OCP E4M3, MAX = 448)
+// in the tile-wise incremental form: for every 128-wide tile of k
+//   m_new = max(m_old, max_tile |a|);   acc = acc * (m_old / m_new) + q(MAX a_tile / m_new) w_tile
+// Each tile is quantised with the running maximum that includes it; earlier tiles keep
+// their codes and are only rescaled.  The result returned is acc * m / MAX, which
+// approximates a @ w^T.  The weights arrive in FP8, as w[N,K] (row n = output channel n).
+//
+// Tiling.  One workgroup of 8 wavefronts owns a 128 (m) x 512 (n) output tile and walks K
+// in steps of 128 (one barrier per step).  The product is computed transposed,
+// C^T = W A_q^T, with v_mfma_f32_32x32x64_f8f6f4 (FP8 x FP8, fp32 accumulate), so each
+// accumulator lane owns one token (one rescale factor per lane).
+//   A operand = W rows: every wavefront streams ITS OWN 64 output channels HBM -> LDS with
+//               direct-to-LDS 128-bit loads into a private ring of three 64-k slots; no
+//               other wavefront reads them, so no barrier guards them.
+//   B operand = quantised tokens: a tile of `a` is loaded into registers one step ahead,
+//               its maximum is merged into the running maximum (4 lanes share a token),
+//               it is scaled, rounded to FP8 with v_cvt_pk_fp8_f32 and written to LDS
+//               (two stages); the rescale factor m_old / m_new travels with the stage.
+// The vector-ALU work of the quantisation is cut into pieces placed between the MFMAs.
+// All waits are hand-placed; loads retire in order, which fixes the counts.
+#include "rf_device.h"
+#include "rf_launch.h"
+
+namespace rf {
+
+namespace {
+
+constexpr int kQWaves = 8;
+constexpr int kQThreads = kQWaves * kWave;
+constexpr int kQM = 128, kQN = 512, kQK = 128;  // K step in elements = bytes of FP8
+constexpr int kQXStageB = kQM * kQK;             // 16 KB: [m][k] bytes, 128-byte rows
+constexpr int kQWSlotB = 64 * 64;                // 4 KB: one wavefront's [64 n][64 k]
+constexpr int kQWRingB = 3 * kQWSlotB;           // per wavefront
+constexpr int kQWBase = 0;
+constexpr int kQXBase = kQWaves * kQWRingB;      // 96 KB
+constexpr int kQCorrBase = kQXBase + 2 * kQXStageB;
+constexpr int kQLdsB = kQCorrBase + 2 * kQM * 4 + kQM * 4;  // + 2 stages of factors + final maxima
+constexpr float kE4M3Max = 448.0f;
+
+// 16-byte slot swizzles
+__device__ __forceinline__ int fQX(int row) { return (row >> 1) & 7; }  // 8 slots per token row
+__device__ __forceinline__ int fQW(int row) { return (row >> 2) & 3; }  // 4 slots per weight row
+
+}  // namespace
+
+__global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
+    const bf16_t* __restrict__ a, const unsigned char* __restrict__ w, bf16_t* __restrict__ c, int M,
+    int K, int N, int64_t lda, int64_t ldw, int64_t ldc, int n_ntiles) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[kQLdsB];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;  // = 64-channel block of the N tile
+  const int i32 = lane & 31;
+  const int hh = lane >> 5;
+
+  // XCD-aware numbering (workgroups are dealt round-robin to the 8 XCDs, each with its own L2)
+  int mt, nt;
+  {
+    const int n_mt = gridDim.x / n_ntiles;
+    if ((n_mt & 3) == 0 && (n_ntiles & 1) == 0) {
+      const int bm = n_mt >> 2, bn = n_ntiles >> 1;
+      const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+      mt = (xcd >> 1) * bm + jj / bn;
+      nt = (xcd & 1) * bn + jj % bn;
+    } else {
+      mt = blockIdx.x / n_ntiles;
+      nt = blockIdx.x % n_ntiles;
+    }
+  }
+  const int m0 = mt * kQM, n0 = nt * kQN;
+  const int nk = K / kQK;  // K is a multiple of 128 (checked by the caller)
+  const int nkk = 2 * nk;  // 64-wide weight tiles
+
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+
+  // ---- token role: a quarter row (32 k) per thread ----
+  const int xrow = tid >> 2;
+  const int xq = tid & 3;
+  const char* abase = reinterpret_cast<const char*>(a + (int64_t)m0 * lda);  // + step * 256 bytes
+  const uint32_t alane_off = (uint32_t)(((int64_t)min(xrow, M - 1 - m0) * lda + 32 * xq) * 2);
+  uint32_t xdst_addr[2][2];  // [stage][half]: LDS byte address of this thread's 16-byte slots
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2) {
+    xdst_addr[0][h2] = lds_base + kQXBase + xrow * 128 + (((2 * xq + h2) ^ fQX(xrow)) << 4);
+    xdst_addr[1][h2] = xdst_addr[0][h2] + kQXStageB;
+  }
+  float* s_corr = reinterpret_cast<float*>(lds + kQCorrBase);          // [2][128]
+  float* s_mfinal = reinterpret_cast<float*>(lds + kQCorrBase) + 2 * kQM;  // [128]
+
+  // ---- weight role: 4 direct-to-LDS loads per wavefront per 64-k tile, 16 channels each ----
+  uint32_t wsrc_off[4];  // byte offset from w + (64-k tile) * 64
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int row = 16 * e + (lane >> 2);  // channel inside the wavefront's 64
+    const int piece = (lane & 3) ^ fQW(row);
+    const int n = min(n0 + 64 * wave + row, N - 1);
+    wsrc_off[e] = (uint32_t)((int64_t)n * ldw + 16 * piece);
+  }
+  const uint32_t wring = __builtin_amdgcn_readfirstlane(lds_base + kQWBase + wave * kQWRingB);
+#define RF_ISSUE_W(TILE, SLOT)                                                                \
+  {                                                                                           \
+    const char* wt_ = reinterpret_cast<const char*>(w) + (int64_t)(TILE) * 64;                \
+    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+      const uint32_t dst_ = wring + (SLOT) * kQWSlotB + e * 1024;                             \
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"            \
+                   :                                                                          \
+                   : "s"(dst_), "v"(wsrc_off[e]), "s"(wt_)                                    \
+                   : "memory");                                                               \
+    }                                                                                         \
+  }
+
+  // ---- fragment read addresses ----
+  // An operand of the 32x32x64 MFMA is 32 bytes per lane: lane (i32, hh) holds bytes
+  // 32 hh .. 32 hh + 31 of row i32 of a 64-k tile = two 16-byte slots.
+  // B operand (tokens): row 32 mi + i32 of the stage, slots 4 kk + 2 hh + {0, 1}
+  uint32_t xaddr[2][2];  // [kk][half] in stage 0; + mi * 32 * 128, + stage
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+      xaddr[kk][h2] = lds_base + kQXBase + i32 * 128 + (((4 * kk + 2 * hh + h2) ^ fQX(i32)) << 4);
+  // A operand (weights): row 32 ni + i32 of the slot, slots 2 hh + {0, 1}
+  uint32_t waddr[2][2];  // [ni][half] in slot 0
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const int row = 32 * ni + i32;
+      waddr[ni][h2] = wring + row * 64 + (((2 * hh + h2) ^ fQW(row)) << 4);
+    }
+
+  f32x16 acc[2][4];  // [ni][mi]: C^T tile (rows = channels, columns = tokens)
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // ---- token tile in registers: 4 x 8 bf16 ----
+  u32x4 xreg[4];
+#define RF_LOAD_X(P, STEP)                                                                    \
+  {                                                                                           \
+    const char* ap_ = abase + (int64_t)(STEP) * (kQK * 2);                                    \
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"                                   \
+                 : "=v"(xreg[P]) : "v"(alane_off), "s"(ap_), "n"(16 * (P)));                  \
+  }
+#define RF_WAIT_X2(P0, P1, PENDING) \
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(xreg[P0]), "+v"(xreg[P1]) : "n"(PENDING));
+  // running state of this thread's token (the 4 lanes of a token hold the same values)
+  float m_run = 0.f, m_done = 0.f;
+  float amax = 0.f, qscale = 0.f;
+  u32x4 qv;  // 16 FP8 codes being assembled
+  auto absmax8 = [&](const u32x4& r) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v = fmaxf(v, fmaxf(fabsf(bf16_lo(r[j])), fabsf(bf16_hi(r[j]))));
+    return v;
+  };
+  // 8 values -> 8 FP8 codes: dwords 2 HALF and 2 HALF + 1 of qv
+#define RF_QUANT8(P, HALF)                                                                    \
+  {                                                                                           \
+    int t0_ = 0, t1_ = 0;                                                                     \
+    t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][0]) * qscale, bf16_hi(xreg[P][0]) * qscale, t0_, false); \
+    t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][1]) * qscale, bf16_hi(xreg[P][1]) * qscale, t0_, true);  \
+    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][2]) * qscale, bf16_hi(xreg[P][2]) * qscale, t1_, false); \
+    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][3]) * qscale, bf16_hi(xreg[P][3]) * qscale, t1_, true);  \
+    qv[2 * (HALF)] = (uint32_t)t0_;                                                           \
+    qv[2 * (HALF) + 1] = (uint32_t)t1_;                                                       \
+  }
+  // merge the tile maximum into the running maximum; scale and rescale factor of the tile
+  auto update_max = [&](int stage_next) {
+    amax = fmaxf(amax, dpp_f32<kDppQuadXor1>(amax));
+    amax = fmaxf(amax, dpp_f32<kDppQuadXor2>(amax));
+    const float m_new = fmaxf(m_run, amax);
+    qscale = m_new > 0.f ? kE4M3Max / m_new : 0.f;  // IEEE division: it decides the FP8 codes
+    const float corr = (m_new == m_run) ? 1.0f : m_run * fast_rcp(m_new);
+    m_run = m_new;
+    if (xq == 0) s_corr[stage_next * kQM + xrow] = corr;
+  };
+#define RF_STORE_X(STAGE, H2) \
+  asm volatile("ds_write_b128 %0, %1" : : "v"(xdst_addr[STAGE][H2]), "v"(qv) : "memory");
+
+  // ---- prologue ----
+  // weight tiles 0 and 1, token tile 0 (quantised into stage 0), token tile 1 in registers,
+  // weight tile 2: the same issue order as in the loop
+  RF_ISSUE_W(0, 0)
+  RF_ISSUE_W(min(1, nkk - 1), 1)
+  RF_LOAD_X(0, 0) RF_LOAD_X(1, 0) RF_LOAD_X(2, 0) RF_LOAD_X(3, 0)
+  RF_WAIT_X2(0, 1, 0) RF_WAIT_X2(2, 3, 0)
+  amax = fmaxf(fmaxf(absmax8(xreg[0]), absmax8(xreg[1])), fmaxf(absmax8(xreg[2]), absmax8(xreg[3])));
+  update_max(0);
+  RF_QUANT8(0, 0)
+  RF_QUANT8(1, 1)
+  RF_STORE_X(0, 0)
+  RF_QUANT8(2, 0)
+  RF_QUANT8(3, 1)
+  RF_STORE_X(0, 1)
+  {
+    const int s1 = min(1, nk - 1);
+    RF_LOAD_X(0, s1) RF_LOAD_X(1, s1) RF_LOAD_X(2, s1) RF_LOAD_X(3, s1)
+  }
+  RF_ISSUE_W(min(2, nkk - 1), 2)
+
+  // ---- main loop ----
+  // Step s multiplies token stage s%2 by weight tiles 2s, 2s+1 (ring slots wslot,
+  // wslot+1), quantises token tile s+1 into stage (s+1)%2, fetches token tile s+2 into
+  // registers and weight tiles 2s+3, 2s+4 into the slots just read.  Every step is the same
+  // straight-line code: past the end of K the prefetches re-read the last tile (nothing
+  // consumes it) and the running maximum is taken from a snapshot made before the surplus
+  // quantisation.  Vector-memory issue order per step: W(2s+3) x4, X piece 0..3, W(2s+4) x4.
+  int wslot = 0;
+  for (int s = 0; s < nk; ++s) {
+    const int st = s & 1;
+    m_done = m_run;  // complete once s is the last step
+    // Weight tile 2s has landed: 12 younger loads (W(2s+1), X x4, W(2s+2)) may still fly.
+    // Our own LDS writes of the previous step are done.
+    asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // token stage st and its factors are complete; stage st^1 is free
+
+    const uint32_t xst = st * kQXStageB;
+    const int slot1 = wslot == 2 ? 0 : wslot + 1;
+    // rescale factors of this step's tile for this lane's four tokens
+    float corr[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const uint32_t ca = lds_base + kQCorrBase + (st * kQM + 32 * mi + i32) * 4;
+      asm volatile("ds_read_b32 %0, %1" : "=v"(corr[mi]) : "v"(ca));
+    }
+
+    i32x8 af[2], bfr[4];
+#define RF_READ32(DST, ADDR0, ADDR1)                                                          \
+  {                                                                                           \
+    u32x4 lo_, hi_;                                                                           \
+    asm volatile("ds_read_b128 %0, %1" : "=v"(lo_) : "v"(ADDR0));                             \
+    asm volatile("ds_read_b128 %0, %1" : "=v"(hi_) : "v"(ADDR1));                             \
+    DST##_lo = lo_;                                                                           \
+    DST##_hi = hi_;                                                                           \
+  }
+    u32x4 a0_lo, a0_hi, a1_lo, a1_hi, b0_lo, b0_hi, b1_lo, b1_hi, b2_lo, b2_hi, b3_lo, b3_hi;
+    // fragment reads of one 64-k tile: 12 x 128 bits
+#define RF_ISSUE_FRAGS(KK, SLOT)                                                              \
+  {                                                                                           \
+    const uint32_t wo_ = (SLOT) * kQWSlotB;                                                   \
+    RF_READ32(a0, waddr[0][0] + wo_, waddr[0][1] + wo_)                                       \
+    RF_READ32(b0, xaddr[KK][0] + xst, xaddr[KK][1] + xst)                                     \
+    RF_READ32(b1, xaddr[KK][0] + xst + 4096, xaddr[KK][1] + xst + 4096)                       \
+    RF_READ32(b2, xaddr[KK][0] + xst + 8192, xaddr[KK][1] + xst + 8192)                       \
+    RF_READ32(b3, xaddr[KK][0] + xst + 12288, xaddr[KK][1] + xst + 12288)                     \
+    RF_READ32(a1, waddr[1][0] + wo_, waddr[1][1] + wo_)                                       \
+  }
+    // wait until at most PENDING LDS operations are in flight; all fragment registers are
+    // tied to the wait so that their uses stay behind it
+#define RF_WAIT_FRAGS(PENDING)                                                                \
+  asm volatile("s_waitcnt lgkmcnt(%12)"                                                       \
+               : "+v"(a0_lo), "+v"(a0_hi), "+v"(a1_lo), "+v"(a1_hi), "+v"(b0_lo), "+v"(b0_hi), \
+                 "+v"(b1_lo), "+v"(b1_hi), "+v"(b2_lo), "+v"(b2_hi), "+v"(b3_lo), "+v"(b3_hi)  \
+               : "n"(PENDING));
+#define RF_PACK(DST, SRC)                                                                     \
+  DST[0] = SRC##_lo[0]; DST[1] = SRC##_lo[1]; DST[2] = SRC##_lo[2]; DST[3] = SRC##_lo[3];     \
+  DST[4] = SRC##_hi[0]; DST[5] = SRC##_hi[1]; DST[6] = SRC##_hi[2]; DST[7] = SRC##_hi[3];
+#define RF_MFMA(NI, MI)                                                                       \
+  acc[NI][MI] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[NI], bfr[MI], acc[NI][MI], \
+                                                                 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+
+    RF_ISSUE_FRAGS(0, wslot)
+    // the factors (issued first) are back once at most the 12 fragment reads are in flight
+    asm volatile("s_waitcnt lgkmcnt(12)" : "+v"(corr[0]), "+v"(corr[1]), "+v"(corr[2]), "+v"(corr[3]));
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      if (__builtin_amdgcn_ballot_w64(corr[mi] != 1.0f) != 0) {  // a maximum moved: rescale (uniform)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[ni][mi][r] *= corr[mi];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- weight tile 2s ----
+    RF_WAIT_FRAGS(0)
+    RF_PACK(af[0], a0) RF_PACK(af[1], a1)
+    RF_PACK(bfr[0], b0) RF_PACK(bfr[1], b1) RF_PACK(bfr[2], b2) RF_PACK(bfr[3], b3)
+    RF_MFMA(0, 0) RF_MFMA(0, 1)
+    RF_WAIT_X2(0, 1, 6)  // token pieces 0, 1 of tile s+1: X2, X3, W(2s+2) may still fly
+    amax = fmaxf(absmax8(xreg[0]), absmax8(xreg[1]));
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(0, 2) RF_MFMA(0, 3)
+    RF_WAIT_X2(2, 3, 4)  // pieces 2, 3: W(2s+2) may still fly
+    amax = fmaxf(amax, fmaxf(absmax8(xreg[2]), absmax8(xreg[3])));
+    update_max(st ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(1, 0) RF_MFMA(1, 1)
+    // every read of ring slot wslot is back: refill it with weight tile 2s+3
+    RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)
+    RF_QUANT8(0, 0)
+    RF_LOAD_X(0, min(s + 2, nk - 1))
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(1, 2) RF_MFMA(1, 3)
+    RF_QUANT8(1, 1)
+    RF_STORE_X(st ^ 1, 0)
+    RF_LOAD_X(1, min(s + 2, nk - 1))
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- weight tile 2s+1 ----
+    RF_ISSUE_FRAGS(1, slot1)
+    RF_WAIT_FRAGS(0)
+    RF_PACK(af[0], a0) RF_PACK(af[1], a1)
+    RF_PACK(bfr[0], b0) RF_PACK(bfr[1], b1) RF_PACK(bfr[2], b2) RF_PACK(bfr[3], b3)
+    RF_MFMA(0, 0) RF_MFMA(0, 1)
+    RF_QUANT8(2, 0)
+    RF_LOAD_X(2, min(s + 2, nk - 1))
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(0, 2) RF_MFMA(0, 3)
+    RF_QUANT8(3, 1)
+    RF_STORE_X(st ^ 1, 1)
+    RF_LOAD_X(3, min(s + 2, nk - 1))
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(1, 0) RF_MFMA(1, 1)
+    RF_ISSUE_W(min(2 * s + 4, nkk - 1), slot1)
+    __builtin_amdgcn_sched_barrier(0);
+    RF_MFMA(1, 2) RF_MFMA(1, 3)
+    __builtin_amdgcn_sched_barrier(0);
+#undef RF_READ32
+#undef RF_ISSUE_FRAGS
+#undef RF_WAIT_FRAGS
+#undef RF_PACK
+#undef RF_MFMA
+    wslot = wslot == 0 ? 2 : wslot - 1;  // (wslot + 2) % 3
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef RF_ISSUE_W
+#undef RF_LOAD_X
+#undef RF_WAIT_X2
+#undef RF_STORE_X
+#undef RF_QUANT8
+
+  // final maxima of the tokens, to the accumulator lanes through LDS
+  if (xq == 0) s_mfinal[xrow] = m_done;
+  __syncthreads();
+
+  // epilogue: c = acc * m / MAX
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int mloc = 32 * mi + i32;
+    const int m = m0 + mloc;
+    const float f = s_mfinal[mloc] * (1.0f / kE4M3Max);
+    if (m >= M) continue;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int n = n0 + 64 * wave + 32 * ni + 8 * r4 + 4 * hh;
+        if (n < N) {
+          u32x2 o2;
+          o2[0] = pack_bf16(acc[ni][mi][4 * r4] * f, acc[ni][mi][4 * r4 + 1] * f);
+          o2[1] = pack_bf16(acc[ni][mi][4 * r4 + 2] * f, acc[ni][mi][4 * r4 + 3] * f);
+          *reinterpret_cast<u32x2*>(c + (int64_t)m * ldc + n) = o2;
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, int K, int N,
+                                 int64_t lda, int64_t ldw, int64_t ldc, hipStream_t s) {
+  const int n_mtiles = (M + kQM - 1) / kQM;
+  const int n_ntiles = (N + kQN - 1) / kQN;
+  const int64_t grid = (int64_t)n_mtiles * n_ntiles;
+  if (grid > INT32_MAX) return hipErrorInvalidValue;
+  // 32-bit lane offsets: inside a 128-token tile of a, inside all of w
+  if ((int64_t)kQM * lda * 2 >= ((int64_t)1 << 32) || (int64_t)N * ldw >= ((int64_t)1 << 32))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fp8_quant_gemm_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, s,
+                     (const bf16_t*)a, (const unsigned char*)w, (bf16_t*)c, M, K, N, lda, ldw, ldc,
+                     n_ntiles);
+  return hipGetLastError();
+}
+
+}  // namespace rf

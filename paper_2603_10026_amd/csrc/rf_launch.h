@@ -59,6 +59,11 @@ hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E
                               int64_t ldx, int64_t ldw, float* prob, int32_t* idx, int64_t ldp,
                               int64_t ldi, float* part, hipStream_t s);
 
+// a [M,K] bf16, w [N,K] FP8 (E4M3), c [M,N] bf16; leading dimensions in elements.
+// K % 128 == 0, N % 8 == 0.
+hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, int K, int N,
+                                 int64_t lda, int64_t ldw, int64_t ldc, hipStream_t s);
+
 // Measurement aids: a plain copy of `bytes` (multiple of 16) and an MFMA-only loop
 // (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
 // workgroups * 256 floats).

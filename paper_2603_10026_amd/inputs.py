@@ -43,6 +43,10 @@ EXTRA_WORKLOADS = {
                            S=2048, hd=8192, E=64, topk=8, score_sigma=1.5),
     "moe_routing_r8": dict(name="moe_routing_bf16_s2048_hd4096_en128_top8", kind="moe_routing", dtype="bf16",
                            S=2048, hd=4096, E=128, topk=8, score_sigma=1.5),
+    "fp8_quant_gemm_q3": dict(name="fp8_quant_gemm_m4096_n3584_k8192", kind="fp8_quant_gemm", dtype="fp8",
+                              M=4096, N=3584, K=8192),
+    "fp8_quant_gemm_q4": dict(name="fp8_quant_gemm_m4096_n8192_k3584", kind="fp8_quant_gemm", dtype="fp8",
+                              M=4096, N=8192, K=3584),
     "variance_v8": dict(name="variance_f32_1024x32768", kind="variance", dtype="f32",
                         bs=1024, l=32768, mu=1.0, sigma=2.0),
 }
@@ -247,6 +251,21 @@ def moe_routing_inputs_device(seed, S, hd, E, score_sigma=1.5, dtype="bf16", dev
     x = _randn_device(gen, (S, hd), dtype, device)
     w = _randn_device(gen, (hd, E), dtype, device, sigma=score_sigma / math.sqrt(hd))
     return x, w
+
+
+def fp8_quant_gemm_inputs_device(seed, M, K, N, device="cuda:0"):
+    """Device-side draw of the same recipe: tokens N(0,1) in bf16 with three entries of eight
+    rows blown up by 30, weights N(0,1) rounded to OCP E4M3 (torch.float8_e4m3fn)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    a = torch.randn((M, K), generator=gen, device=device, dtype=torch.float32)
+    rows = torch.randperm(M, generator=gen, device=device)[:min(8, M)]
+    cols = torch.randint(0, K, (rows.numel(), 3), generator=gen, device=device)
+    a[rows[:, None], cols] *= 30.0
+    a = a.to(torch.bfloat16)
+    w = torch.randn((N, K), generator=gen, device=device, dtype=torch.float32).clamp_(-448.0, 448.0)
+    return a, w.to(torch.float8_e4m3fn)
 
 
 def rmsnorm_gemm_inputs_device(seed, M, K, N, w_sigma=0.02, dtype="bf16", device="cuda:0"):

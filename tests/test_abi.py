@@ -176,6 +176,24 @@ def test_moe_routing_validation(lib):
     assert B.describe_cascade("rf_moe_routing") == [(0, 0), (2, 1), (0, 0)]      # max, sum, top-k (max-type)
 
 
+def test_fp8_quant_gemm_validation(lib):
+    F8 = B.RF_FP8_E4M3
+    a, w, c = _desc([64, 256]), _desc([128, 256], F8), _desc([64, 128])
+    f = lib.rf_fp8_quant_gemm
+    assert f(None, _r(w), _r(c), None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(a), _r(_desc([128, 128], F8)), _r(c), None) == B.RF_ERR_INVALID_ARG     # K mismatch
+    assert f(_r(a), _r(w), _r(_desc([64, 120])), None) == B.RF_ERR_INVALID_ARG
+    assert f(_r(a), _r(_desc([128, 256])), _r(c), None) == B.RF_ERR_UNSUPPORTED         # weights must be FP8
+    assert f(_r(_desc([64, 256], F8)), _r(w), _r(c), None) == B.RF_ERR_UNSUPPORTED      # tokens must be bf16
+    assert f(_r(_desc([64, 192])), _r(_desc([128, 192], F8)), _r(c), None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(a), _r(_desc([124, 256], F8)), _r(_desc([64, 124])), None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(a), _r(_desc([128, 256], F8, data=0x1004)), _r(c), None) == B.RF_ERR_ALIGNMENT
+    assert f(_r(_desc([0, 256], data=None)), _r(w), _r(_desc([0, 128], data=None)), None) == B.RF_OK
+    # FP8 is refused where an entry point does not ask for it
+    assert lib.rf_safe_softmax(_r(_desc([4, 64], F8)), _r(_desc([4, 64], F8)), -1, None) == B.RF_ERR_UNSUPPORTED
+    assert B.describe_cascade("rf_fp8_quant_gemm") == [(0, 0), (2, 1)]                  # max, then sum
+
+
 def test_binding_descriptor_from_torch_tensor():
     t = torch.zeros((3, 4, 8), dtype=torch.bfloat16)[:, 1:3]
     d = B.tensor_desc(t)

@@ -394,3 +394,42 @@ def test_moe_routing_exact_ties_and_pitched_outputs(rf):
     np.testing.assert_array_equal(idx, i_ref)                 # bit-exact decisions, ties included
     np.testing.assert_allclose(prob, p_ref, rtol=2e-5, atol=1e-8)
     assert list(idx[5]) == list(range(topk)) and np.all(prob[5] == np.float32(1.0 / E))
+
+
+# ------------------------------------------------- FP8 per-token quant + GEMM
+def _fp8_tensor(w_bits):
+    return torch.from_numpy(np.ascontiguousarray(w_bits)).to(DEV).view(torch.float8_e4m3fn)
+
+
+@pytest.mark.parametrize("M,K,N", [(128, 256, 512), (77, 128, 72), (300, 512, 264), (1, 128, 8), (256, 1024, 1032),
+                                   (130, 384, 520)])
+def test_fp8_quant_gemm_shapes(rf, M, K, N):
+    say(f"fp8_quant_gemm M{M} K{K} N{N}")
+    a, w, w_bits = I.fp8_quant_gemm_inputs(I.SEED_BASE + 7, M, K, N)
+    c = rf.rf_fp8_quant_gemm(I.to_torch(a, "bf16", DEV), _fp8_tensor(w_bits))
+    torch.cuda.synchronize()
+    # the oracle runs the same algorithm: segments of 128, each quantised with its running maximum
+    check(c, O.fp8_quant_gemm(a, w, 128), "bf16", "fp8_quant_gemm")
+
+
+def test_fp8_quant_gemm_special_rows_and_pitched_output(rf):
+    say("fp8_quant_gemm: zero token, late maximum, maximum in the first tile, pitched c")
+    M, K, N = 64, 512, 128
+    a, w, w_bits = I.fp8_quant_gemm_inputs(93, M, K, N, outlier_rows=0)
+    a[0] = 0.0                                  # all-zero token -> zeros
+    a[1, K - 1] = 200.0                         # maximum arrives in the last tile: every tile rescales
+    a[2, 3] = 200.0                             # maximum in the first tile: equals the two-pass definition
+    a[3] = I.bf16_round(a[3] * 1e-3)            # small token: its own scale
+    a[4] = I.bf16_round(a[4] * 1e3)
+    cbig = torch.zeros((M, 2 * N), dtype=torch.bfloat16, device=DEV)
+    rf.rf_fp8_quant_gemm(I.to_torch(a, "bf16", DEV), _fp8_tensor(w_bits), c=cbig[:, N:])
+    torch.cuda.synchronize()
+    ref = O.fp8_quant_gemm(a, w, 128)
+    out = I.to_numpy(cbig[:, N:])
+    assert float(cbig[:, :N].abs().max()) == 0.0
+    assert np.all(out[0] == 0.0)
+    for i in range(M):                          # every token against its own scale
+        s = np.max(np.abs(ref[i]))
+        assert np.max(np.abs(out[i] - ref[i])) <= 2e-2 * s + 1e-30, i
+    two = O.fp8_quant_gemm_twopass(a, w)
+    assert np.max(np.abs(out[2] - two[2])) <= 2e-2 * np.max(np.abs(two[2]))

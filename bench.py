@@ -12,6 +12,7 @@ After the timed steps the paper's further cascades are timed one kernel at a tim
 (``further_cascades``; they are not part of a step):
   x1  rf_variance                  f32   X[1024,32768]
   x2  rf_moe_routing               bf16  tokens 2048; hd 8192 x 64 experts, hd 4096 x 128 experts; top 8
+  x3  rf_fp8_quant_gemm            bf16 tokens x FP8 weights  4096 x 3584 x 8192 and 4096 x 8192 x 3584
 Inputs are generated on the device from fixed seeds before the timed region.
 The memory-bound workloads (w1, w3) rotate over three buffer sets so that the
 last-level cache cannot serve repeated reads.
@@ -66,7 +67,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1", "x2"}
+    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1", "x2", "x3"}
     W = I.WORKLOADS
     seed = lambda i: I.SEED_BASE + i
 
@@ -286,6 +287,24 @@ def main():
             rooflines.append(dict(kernel=label, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                                   frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic.get(label), us=round(d["avg"], 2)))
             del sets, ws
+    if "x3" in only:
+        PEAK_FP8_TFLOPS = 5000.0      # dense fp8 MFMA, published
+        for key in ("fp8_quant_gemm_q3", "fp8_quant_gemm_q4"):
+            c = I.EXTRA_WORKLOADS[key]
+            aa, ww = I.fp8_quant_gemm_inputs_device(seed(7), c["M"], c["K"], c["N"], dev)
+            cc = torch.empty((c["M"], c["N"]), dtype=torch.bfloat16, device=dev)
+            d = time_launches(lambda i, aa=aa, ww=ww, cc=cc: rf.rf_fp8_quant_gemm(aa, ww, c=cc), args.steps, args.warmup)
+            fl = 2.0 * c["M"] * c["K"] * c["N"]
+            ach = fl / (d["avg"] * 1e-6) / 1e12
+            label = "x3_" + key
+            further[label] = dict(workload=c["name"], us_avg=round(d["avg"], 2), us_med=round(d["med"], 2),
+                                  us_min=round(d["min"], 2), bound="mfma", TFLOPs=round(ach, 1),
+                                  frac=round(ach / PEAK_FP8_TFLOPS, 4), algorithmic_flops=fl,
+                                  note="fraction of the published dense fp8 peak (5 PFLOP/s)")
+            rooflines.append(dict(kernel=label, bound="mfma", achieved=round(ach, 1), peak=PEAK_FP8_TFLOPS,
+                                  unit="TFLOP/s", frac=round(ach / PEAK_FP8_TFLOPS, 4), traffic=traffic.get(label),
+                                  us=round(d["avg"], 2)))
+            del aa, ww, cc
 
     # -------------------------------------------- measured ceilings (context, not the peaks)
     def timed(fn, n):
@@ -313,6 +332,8 @@ def main():
                     mfma_bf16_constant_operands_TFLOPs=round(fl / t_const / 1e12, 1),
                     note="plain 256 MiB copy kernel; MFMA-only 32x32x16 bf16 loop, 512 workgroups x 4 wavefronts")
     for r in rooflines:
+        if r["bound"] == "mfma" and r["peak"] != PEAK_BF16_TFLOPS:
+            continue            # no measured ceiling for the fp8 matrix pipe
         ceil = ceilings["hbm_copy_GBps"] if r["bound"] == "hbm" else ceilings["mfma_bf16_random_operands_TFLOPs"]
         r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
 

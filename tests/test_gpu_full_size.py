@@ -189,3 +189,19 @@ def test_moe_routing_full(rf, key):
         assert np.delete(p[i], idx[i]).max() <= ps[-1] + delta
     np.testing.assert_allclose(prob, np.take_along_axis(soft, idx, axis=1), rtol=2e-4, atol=1e-7)
     assert float(np.max(np.abs(np.sort(prob, axis=1) - np.sort(p_ref, axis=1)))) <= 1e-5 * float(np.max(p_ref)) + 1e-7
+
+
+@pytest.mark.parametrize("key", ["fp8_quant_gemm_q3", "fp8_quant_gemm_q4"])
+def test_fp8_quant_gemm_full(rf, key):
+    c = I.EXTRA_WORKLOADS[key]
+    say(c["name"])
+    a, w = I.fp8_quant_gemm_inputs_device(I.SEED_BASE + 7, c["M"], c["K"], c["N"], DEV)
+    out = rf.rf_fp8_quant_gemm(a, w)
+    torch.cuda.synchronize()
+    # sampled token rows (tokens are independent): every 61st row plus the tile edges
+    rows = sorted(set(list(range(0, c["M"], 61)) + [127, 128, c["M"] - 1]))
+    ah = I.to_numpy(a[rows]).astype(np.float32)
+    wh = I.to_numpy(w.to(torch.float32))
+    ref = O.fp8_quant_gemm(ah, wh, 128)
+    check_rows(I.to_numpy(out[rows]), ref, 2e-2, "fp8_quant_gemm", row_tol=2e-2)
+    assert bool(torch.isfinite(out.float()).all())

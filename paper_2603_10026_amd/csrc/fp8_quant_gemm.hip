@@ -76,16 +76,19 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
 
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
-  // ---- token role: a quarter row (32 k) per thread ----
+  // ---- token role: four lanes per token row, 32 k per thread in four 8-value pieces ----
+  // Load P of a thread covers k = 32 P + 8 xq .. + 7, so that one load instruction reads 64
+  // contiguous bytes of every row it touches (the four lanes of a row side by side).
   const int xrow = tid >> 2;
   const int xq = tid & 3;
   const char* abase = reinterpret_cast<const char*>(a + (int64_t)m0 * lda);  // + step * 256 bytes
-  const uint32_t alane_off = (uint32_t)(((int64_t)min(xrow, M - 1 - m0) * lda + 32 * xq) * 2);
-  uint32_t xdst_addr[2][2];  // [stage][half]: LDS byte address of this thread's 16-byte slots
+  const uint32_t alane_off = (uint32_t)(((int64_t)min(xrow, M - 1 - m0) * lda + 8 * xq) * 2);
+  uint32_t xdst_addr[2][4];  // [stage][piece]: LDS byte address of the piece's 8 FP8 codes
 #pragma unroll
-  for (int h2 = 0; h2 < 2; ++h2) {
-    xdst_addr[0][h2] = lds_base + kQXBase + xrow * 128 + (((2 * xq + h2) ^ fQX(xrow)) << 4);
-    xdst_addr[1][h2] = xdst_addr[0][h2] + kQXStageB;
+  for (int p4 = 0; p4 < 4; ++p4) {
+    xdst_addr[0][p4] = lds_base + kQXBase + xrow * 128 +
+                       (((2 * p4 + (xq >> 1)) ^ fQX(xrow)) << 4) + 8 * (xq & 1);
+    xdst_addr[1][p4] = xdst_addr[0][p4] + kQXStageB;
   }
   float* s_corr = reinterpret_cast<float*>(lds + kQCorrBase);          // [2][128]
   float* s_mfinal = reinterpret_cast<float*>(lds + kQCorrBase) + 2 * kQM;  // [128]
@@ -146,30 +149,42 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   {                                                                                           \
     const char* ap_ = abase + (int64_t)(STEP) * (kQK * 2);                                    \
     asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"                                   \
-                 : "=v"(xreg[P]) : "v"(alane_off), "s"(ap_), "n"(16 * (P)));                  \
+                 : "=v"(xreg[P]) : "v"(alane_off), "s"(ap_), "n"(64 * (P)));                  \
   }
 #define RF_WAIT_X2(P0, P1, PENDING) \
   asm volatile("s_waitcnt vmcnt(%2)" : "+v"(xreg[P0]), "+v"(xreg[P1]) : "n"(PENDING));
   // running state of this thread's token (the 4 lanes of a token hold the same values)
   float m_run = 0.f, m_done = 0.f;
   float amax = 0.f, qscale = 0.f;
-  u32x4 qv;  // 16 FP8 codes being assembled
+  unsigned amax_bits = 0;  // packed pair of running 16-bit maxima of the tile
+  // max |x| of 8 bf16 values.  For non-negative values the bf16 bit patterns order like
+  // unsigned integers, so the sign bits are cleared and the maximum is taken on packed
+  // 16-bit integers, two values per operation; the result is a packed pair to be folded.
+  typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
   auto absmax8 = [&](const u32x4& r) {
-    float v = 0.f;
+    u16x2 v = __builtin_bit_cast(u16x2, r[0] & 0x7fff7fffu);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v = fmaxf(v, fmaxf(fabsf(bf16_lo(r[j])), fabsf(bf16_hi(r[j]))));
+    for (int j = 1; j < 4; ++j)
+      v = __builtin_elementwise_max(v, __builtin_bit_cast(u16x2, r[j] & 0x7fff7fffu));
     return v;
   };
-  // 8 values -> 8 FP8 codes: dwords 2 HALF and 2 HALF + 1 of qv
-#define RF_QUANT8(P, HALF)                                                                    \
+  auto fold_max = [&](u16x2 v) {  // packed pair -> fp32 value of the larger bf16
+    const unsigned short m16 = v[0] > v[1] ? v[0] : v[1];
+    return __uint_as_float((uint32_t)m16 << 16);
+  };
+  // piece P: 8 values -> 8 FP8 codes -> LDS (raw write: the compiler would order an ordinary
+  // one behind the direct-to-LDS loads in flight)
+#define RF_QUANT_STORE(P, STAGE)                                                              \
   {                                                                                           \
     int t0_ = 0, t1_ = 0;                                                                     \
     t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][0]) * qscale, bf16_hi(xreg[P][0]) * qscale, t0_, false); \
     t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][1]) * qscale, bf16_hi(xreg[P][1]) * qscale, t0_, true);  \
     t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][2]) * qscale, bf16_hi(xreg[P][2]) * qscale, t1_, false); \
     t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][3]) * qscale, bf16_hi(xreg[P][3]) * qscale, t1_, true);  \
-    qv[2 * (HALF)] = (uint32_t)t0_;                                                           \
-    qv[2 * (HALF) + 1] = (uint32_t)t1_;                                                       \
+    u32x2 q2_;                                                                                \
+    q2_[0] = (uint32_t)t0_;                                                                   \
+    q2_[1] = (uint32_t)t1_;                                                                   \
+    asm volatile("ds_write_b64 %0, %1" : : "v"(xdst_addr[STAGE][P]), "v"(q2_) : "memory");    \
   }
   // merge the tile maximum into the running maximum; scale and rescale factor of the tile
   auto update_max = [&](int stage_next) {
@@ -181,29 +196,24 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     m_run = m_new;
     if (xq == 0) s_corr[stage_next * kQM + xrow] = corr;
   };
-#define RF_STORE_X(STAGE, H2) \
-  asm volatile("ds_write_b128 %0, %1" : : "v"(xdst_addr[STAGE][H2]), "v"(qv) : "memory");
 
   // ---- prologue ----
-  // weight tiles 0 and 1, token tile 0 (quantised into stage 0), token tile 1 in registers,
-  // weight tile 2: the same issue order as in the loop
+  // weight tile 0, token tile 0 (quantised into stage 0), then token tile 1 and weight
+  // tiles 1, 2 in the issue order of a loop step
   RF_ISSUE_W(0, 0)
-  RF_ISSUE_W(min(1, nkk - 1), 1)
   RF_LOAD_X(0, 0) RF_LOAD_X(1, 0) RF_LOAD_X(2, 0) RF_LOAD_X(3, 0)
   RF_WAIT_X2(0, 1, 0) RF_WAIT_X2(2, 3, 0)
-  amax = fmaxf(fmaxf(absmax8(xreg[0]), absmax8(xreg[1])), fmaxf(absmax8(xreg[2]), absmax8(xreg[3])));
+  amax = fold_max(__builtin_elementwise_max(__builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])),
+                                            __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
   update_max(0);
-  RF_QUANT8(0, 0)
-  RF_QUANT8(1, 1)
-  RF_STORE_X(0, 0)
-  RF_QUANT8(2, 0)
-  RF_QUANT8(3, 1)
-  RF_STORE_X(0, 1)
+  RF_QUANT_STORE(0, 0) RF_QUANT_STORE(1, 0) RF_QUANT_STORE(2, 0) RF_QUANT_STORE(3, 0)
   {
     const int s1 = min(1, nk - 1);
-    RF_LOAD_X(0, s1) RF_LOAD_X(1, s1) RF_LOAD_X(2, s1) RF_LOAD_X(3, s1)
+    RF_LOAD_X(0, s1) RF_LOAD_X(1, s1)
+    RF_ISSUE_W(min(1, nkk - 1), 1)
+    RF_LOAD_X(2, s1) RF_LOAD_X(3, s1)
+    RF_ISSUE_W(min(2, nkk - 1), 2)
   }
-  RF_ISSUE_W(min(2, nkk - 1), 2)
 
   // ---- main loop ----
   // Step s multiplies token stage s%2 by weight tiles 2s, 2s+1 (ring slots wslot,
@@ -211,7 +221,7 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   // registers and weight tiles 2s+3, 2s+4 into the slots just read.  Every step is the same
   // straight-line code: past the end of K the prefetches re-read the last tile (nothing
   // consumes it) and the running maximum is taken from a snapshot made before the surplus
-  // quantisation.  Vector-memory issue order per step: W(2s+3) x4, X piece 0..3, W(2s+4) x4.
+  // quantisation.  Vector-memory issue order per step: X0, X1, W(2s+3) x4, X2, X3, W(2s+4) x4.
   int wslot = 0;
   for (int s = 0; s < nk; ++s) {
     const int st = s & 1;
@@ -231,42 +241,45 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
       asm volatile("ds_read_b32 %0, %1" : "=v"(corr[mi]) : "v"(ca));
     }
 
-    i32x8 af[2], bfr[4];
-#define RF_READ32(DST, ADDR0, ADDR1)                                                          \
-  {                                                                                           \
-    u32x4 lo_, hi_;                                                                           \
-    asm volatile("ds_read_b128 %0, %1" : "=v"(lo_) : "v"(ADDR0));                             \
-    asm volatile("ds_read_b128 %0, %1" : "=v"(hi_) : "v"(ADDR1));                             \
-    DST##_lo = lo_;                                                                           \
-    DST##_hi = hi_;                                                                           \
-  }
+    // Fragment registers: one 32-byte operand = two 128-bit halves.  The fragments of the
+    // second weight tile are fetched into the registers of the first as those fall dead
+    // (an operand is dead once the last MFMA that reads it has been issued; LDS data
+    // comes back long after that MFMA has read its sources).
     u32x4 a0_lo, a0_hi, a1_lo, a1_hi, b0_lo, b0_hi, b1_lo, b1_hi, b2_lo, b2_hi, b3_lo, b3_hi;
-    // fragment reads of one 64-k tile: 12 x 128 bits
-#define RF_ISSUE_FRAGS(KK, SLOT)                                                              \
-  {                                                                                           \
-    const uint32_t wo_ = (SLOT) * kQWSlotB;                                                   \
-    RF_READ32(a0, waddr[0][0] + wo_, waddr[0][1] + wo_)                                       \
-    RF_READ32(b0, xaddr[KK][0] + xst, xaddr[KK][1] + xst)                                     \
-    RF_READ32(b1, xaddr[KK][0] + xst + 4096, xaddr[KK][1] + xst + 4096)                       \
-    RF_READ32(b2, xaddr[KK][0] + xst + 8192, xaddr[KK][1] + xst + 8192)                       \
-    RF_READ32(b3, xaddr[KK][0] + xst + 12288, xaddr[KK][1] + xst + 12288)                     \
-    RF_READ32(a1, waddr[1][0] + wo_, waddr[1][1] + wo_)                                       \
-  }
-    // wait until at most PENDING LDS operations are in flight; all fragment registers are
-    // tied to the wait so that their uses stay behind it
-#define RF_WAIT_FRAGS(PENDING)                                                                \
-  asm volatile("s_waitcnt lgkmcnt(%12)"                                                       \
-               : "+v"(a0_lo), "+v"(a0_hi), "+v"(a1_lo), "+v"(a1_hi), "+v"(b0_lo), "+v"(b0_hi), \
-                 "+v"(b1_lo), "+v"(b1_hi), "+v"(b2_lo), "+v"(b2_hi), "+v"(b3_lo), "+v"(b3_hi)  \
+#define RF_READ32(DST, ADDR0, ADDR1, OFF)                                                     \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST##_lo) : "v"(ADDR0), "n"(OFF));      \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST##_hi) : "v"(ADDR1), "n"(OFF));
+    // per-step base addresses; token tile mi and channel tile ni are immediate offsets
+    const uint32_t xa00 = xaddr[0][0] + xst, xa01 = xaddr[0][1] + xst;
+    const uint32_t xa10 = xaddr[1][0] + xst, xa11 = xaddr[1][1] + xst;
+    const uint32_t wa0_0 = waddr[0][0] + wslot * kQWSlotB, wa0_1 = waddr[0][1] + wslot * kQWSlotB;
+    const uint32_t wa1_0 = waddr[0][0] + slot1 * kQWSlotB, wa1_1 = waddr[0][1] + slot1 * kQWSlotB;
+#define RF_READ_A(DST, NI, TILE) RF_READ32(DST, wa##TILE##_0, wa##TILE##_1, (NI) * 32 * 64)
+#define RF_READ_B(DST, MI, KK) RF_READ32(DST, xa##KK##0, xa##KK##1, (MI) * 4096)
+    // wait until at most PENDING LDS operations are in flight; the named operand is tied
+    // to the wait so that its uses stay behind it
+#define RF_WAIT2(X, Y, PENDING)                                                               \
+  asm volatile("s_waitcnt lgkmcnt(%4)"                                                        \
+               : "+v"(X##_lo), "+v"(X##_hi), "+v"(Y##_lo), "+v"(Y##_hi)                       \
                : "n"(PENDING));
-#define RF_PACK(DST, SRC)                                                                     \
-  DST[0] = SRC##_lo[0]; DST[1] = SRC##_lo[1]; DST[2] = SRC##_lo[2]; DST[3] = SRC##_lo[3];     \
-  DST[4] = SRC##_hi[0]; DST[5] = SRC##_hi[1]; DST[6] = SRC##_hi[2]; DST[7] = SRC##_hi[3];
-#define RF_MFMA(NI, MI)                                                                       \
-  acc[NI][MI] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[NI], bfr[MI], acc[NI][MI], \
-                                                                 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+#define RF_WAIT1(X, PENDING) \
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(X##_lo), "+v"(X##_hi) : "n"(PENDING));
+#define RF_MFMA(NI, MI, A, B)                                                                 \
+  {                                                                                           \
+    i32x8 av_, bv_;                                                                           \
+    av_[0] = A##_lo[0]; av_[1] = A##_lo[1]; av_[2] = A##_lo[2]; av_[3] = A##_lo[3];           \
+    av_[4] = A##_hi[0]; av_[5] = A##_hi[1]; av_[6] = A##_hi[2]; av_[7] = A##_hi[3];           \
+    bv_[0] = B##_lo[0]; bv_[1] = B##_lo[1]; bv_[2] = B##_lo[2]; bv_[3] = B##_lo[3];           \
+    bv_[4] = B##_hi[0]; bv_[5] = B##_hi[1]; bv_[6] = B##_hi[2]; bv_[7] = B##_hi[3];           \
+    acc[NI][MI] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                            \
+        av_, bv_, acc[NI][MI], 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);                           \
+  }
+#define RF_FENCE __builtin_amdgcn_sched_barrier(0);
 
-    RF_ISSUE_FRAGS(0, wslot)
+    // fragments of weight tile 2s: 12 x 128 bits, in the order of their first use
+    RF_READ_A(a0, 0, 0)
+    RF_READ_B(b0, 0, 0) RF_READ_B(b1, 1, 0) RF_READ_B(b2, 2, 0) RF_READ_B(b3, 3, 0)
+    RF_READ_A(a1, 1, 0)
     // the factors (issued first) are back once at most the 12 fragment reads are in flight
     asm volatile("s_waitcnt lgkmcnt(12)" : "+v"(corr[0]), "+v"(corr[1]), "+v"(corr[2]), "+v"(corr[3]));
 #pragma unroll
@@ -278,65 +291,88 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
           for (int r = 0; r < 16; ++r) acc[ni][mi][r] *= corr[mi];
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
+    RF_FENCE
 
     // ---- weight tile 2s ----
-    RF_WAIT_FRAGS(0)
-    RF_PACK(af[0], a0) RF_PACK(af[1], a1)
-    RF_PACK(bfr[0], b0) RF_PACK(bfr[1], b1) RF_PACK(bfr[2], b2) RF_PACK(bfr[3], b3)
-    RF_MFMA(0, 0) RF_MFMA(0, 1)
-    RF_WAIT_X2(0, 1, 6)  // token pieces 0, 1 of tile s+1: X2, X3, W(2s+2) may still fly
-    amax = fmaxf(absmax8(xreg[0]), absmax8(xreg[1]));
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(0, 2) RF_MFMA(0, 3)
+    RF_WAIT2(a0, b0, 8)
+    RF_MFMA(0, 0, a0, b0)
+    RF_WAIT_X2(0, 1, 10)  // token pieces 0, 1 of tile s+1: W(2s+1), X2, X3, W(2s+2) may still fly
+    amax_bits = __builtin_bit_cast(unsigned, __builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])));
+    RF_FENCE
+    RF_WAIT1(b1, 6)
+    RF_MFMA(0, 1, a0, b1)
     RF_WAIT_X2(2, 3, 4)  // pieces 2, 3: W(2s+2) may still fly
-    amax = fmaxf(amax, fmaxf(absmax8(xreg[2]), absmax8(xreg[3])));
+    amax = fold_max(__builtin_elementwise_max(
+        __builtin_bit_cast(u16x2, amax_bits), __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
     update_max(st ^ 1);
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(1, 0) RF_MFMA(1, 1)
-    // every read of ring slot wslot is back: refill it with weight tile 2s+3
-    RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)
-    RF_QUANT8(0, 0)
+    RF_FENCE
+    RF_WAIT1(b2, 4)
+    RF_MFMA(0, 2, a0, b2)
+    RF_FENCE
+    RF_WAIT1(b3, 2)
+    RF_MFMA(0, 3, a0, b3)
+    RF_FENCE
+    RF_WAIT1(a1, 0)  // every read of ring slot wslot is back
+    RF_QUANT_STORE(0, st ^ 1)
     RF_LOAD_X(0, min(s + 2, nk - 1))
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(1, 2) RF_MFMA(1, 3)
-    RF_QUANT8(1, 1)
-    RF_STORE_X(st ^ 1, 0)
+    RF_QUANT_STORE(1, st ^ 1)
     RF_LOAD_X(1, min(s + 2, nk - 1))
-    __builtin_amdgcn_sched_barrier(0);
+    RF_READ_A(a0, 0, 1)       // first operand of weight tile 2s+1
+    RF_MFMA(1, 0, a1, b0)
+    RF_READ_B(b0, 0, 1)
+    RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)  // refill the slot just read
+    RF_FENCE
+    RF_MFMA(1, 1, a1, b1)
+    RF_READ_B(b1, 1, 1)
+    RF_FENCE
+    RF_MFMA(1, 2, a1, b2)
+    RF_READ_B(b2, 2, 1)
+    RF_FENCE
+    RF_MFMA(1, 3, a1, b3)
+    RF_READ_B(b3, 3, 1)
+    RF_READ_A(a1, 1, 1)
+    RF_FENCE
 
     // ---- weight tile 2s+1 ----
-    RF_ISSUE_FRAGS(1, slot1)
-    RF_WAIT_FRAGS(0)
-    RF_PACK(af[0], a0) RF_PACK(af[1], a1)
-    RF_PACK(bfr[0], b0) RF_PACK(bfr[1], b1) RF_PACK(bfr[2], b2) RF_PACK(bfr[3], b3)
-    RF_MFMA(0, 0) RF_MFMA(0, 1)
-    RF_QUANT8(2, 0)
+    // LDS operations in flight, oldest first: two piece writes, a0, b0, b1, b2, b3, a1
+    RF_WAIT2(a0, b0, 8)
+    RF_MFMA(0, 0, a0, b0)
+    RF_FENCE
+    RF_WAIT1(b1, 6)
+    RF_MFMA(0, 1, a0, b1)
+    RF_FENCE
+    RF_WAIT1(b2, 4)
+    RF_MFMA(0, 2, a0, b2)
+    RF_FENCE
+    RF_WAIT1(b3, 2)
+    RF_MFMA(0, 3, a0, b3)
+    RF_FENCE
+    RF_WAIT1(a1, 0)  // every read of ring slot slot1 is back
+    RF_QUANT_STORE(2, st ^ 1)
     RF_LOAD_X(2, min(s + 2, nk - 1))
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(0, 2) RF_MFMA(0, 3)
-    RF_QUANT8(3, 1)
-    RF_STORE_X(st ^ 1, 1)
+    RF_QUANT_STORE(3, st ^ 1)
     RF_LOAD_X(3, min(s + 2, nk - 1))
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(1, 0) RF_MFMA(1, 1)
+    RF_MFMA(1, 0, a1, b0)
     RF_ISSUE_W(min(2 * s + 4, nkk - 1), slot1)
-    __builtin_amdgcn_sched_barrier(0);
-    RF_MFMA(1, 2) RF_MFMA(1, 3)
-    __builtin_amdgcn_sched_barrier(0);
+    RF_FENCE
+    RF_MFMA(1, 1, a1, b1)
+    RF_MFMA(1, 2, a1, b2)
+    RF_MFMA(1, 3, a1, b3)
+    RF_FENCE
 #undef RF_READ32
-#undef RF_ISSUE_FRAGS
-#undef RF_WAIT_FRAGS
-#undef RF_PACK
+#undef RF_READ_A
+#undef RF_READ_B
+#undef RF_WAIT2
+#undef RF_WAIT1
 #undef RF_MFMA
+#undef RF_FENCE
     wslot = wslot == 0 ? 2 : wslot - 1;  // (wslot + 2) % 3
   }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #undef RF_ISSUE_W
 #undef RF_LOAD_X
 #undef RF_WAIT_X2
-#undef RF_STORE_X
-#undef RF_QUANT8
+#undef RF_QUANT_STORE
 
   // final maxima of the tokens, to the accumulator lanes through LDS
   if (xq == 0) s_mfinal[xrow] = m_done;

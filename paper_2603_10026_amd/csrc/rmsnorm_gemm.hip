@@ -113,7 +113,17 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
   }
   const uint32_t wdst0 = __builtin_amdgcn_readfirstlane(lds_base + wave * 8 * kWRowB);
   const int64_t wstep_b = (int64_t)kBKK * ldw * 2;
-#define RF_ISSUE_W(STEP, STAGE)                                                                {                                                                                              const char* wt_ = reinterpret_cast<const char*>(w) + (int64_t)(STEP) * wstep_b;              _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                                const uint32_t dst_ = wdst0 + (STAGE) * kWTileB + e * kWRowB;                                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                           : : "s"(dst_), "v"(wsrc_off[e]), "s"(wt_) : "memory");                        }                                                                                          }
+#define RF_ISSUE_W(STEP, STAGE)                                                              \
+  {                                                                                          \
+    const char* wt_ = reinterpret_cast<const char*>(w) + (int64_t)(STEP) * wstep_b;          \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                          \
+      const uint32_t dst_ = wdst0 + (STAGE) * kWTileB + e * kWRowB;                          \
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"          \
+                   :                                                                         \
+                   : "s"(dst_), "v"(wsrc_off[e]), "s"(wt_)                                   \
+                   : "memory");                                                              \
+    }                                                                                        \
+  }
 
   // ---- fragment read addresses (LDS byte addresses in stage 0) ----
   // B operand (X g): lane (i32, hh) of column tile mi reads row 32mi + i32, slot 2kk + hh

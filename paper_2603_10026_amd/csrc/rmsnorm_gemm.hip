@@ -74,6 +74,11 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
       const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
       mt = (xcd >> 1) * bm + jj / bn;
       nt = (xcd & 1) * bn + jj % bn;
+    } else if ((gridDim.x & 7) == 0) {
+      // XCD x owns a run of consecutive tiles in row-major order (a few whole tile rows)
+      const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+      mt = t / n_ntiles;
+      nt = t % n_ntiles;
     } else {
       mt = blockIdx.x / n_ntiles;
       nt = blockIdx.x % n_ntiles;

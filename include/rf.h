@@ -207,6 +207,22 @@ RF_API rf_status rf_rmsnorm_gemm(const rf_tensor* x, const rf_tensor* g, const r
                           rf_tensor* y, float eps, rf_stream stream);
 
 /*
+ * Fusion-level study of the safe-softmax cascade (Section 5.3 of the paper: the same cascade
+ * fused at different levels of the reduction tree).  Same result as rf_safe_softmax on
+ * x, y : [rows, n] bf16, n % 8 == 0, n <= 8192, rows 16-byte aligned; what differs is where
+ * the two reductions are fused:
+ *   level 0  not fused: three kernels (max, sum of exponentials, normalise), three reads of x;
+ *            ml_buf: device memory for 2 * rows floats (the row maxima and sums)
+ *   level 1  fused per lane: every lane runs the incremental form over its own elements,
+ *            lane states merged with the level-k expression
+ *   level 2  fused per wavefront: what rf_safe_softmax runs for these shapes
+ *   level 3  fused per workgroup: lane states merged across four wavefronts through LDS
+ * ml_buf is ignored for levels 1..3.
+ */
+RF_API rf_status rf_diag_softmax_level(const rf_tensor* x, rf_tensor* y, int level, float* ml_buf,
+                                       rf_stream stream);
+
+/*
  * Measurement aids, not part of the cascaded-reduction path.  They provide the two
  * measured ceilings that roofline fractions are reported next to (a plain copy kernel for
  * HBM, an MFMA-only loop for the matrix pipe) and the reference dispatch that scales the

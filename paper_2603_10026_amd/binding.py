@@ -33,6 +33,7 @@ ENTRY_POINTS = (
     "rf_moe_routing_workspace_bytes",
     "rf_moe_routing",
     "rf_fp8_quant_gemm",
+    "rf_diag_softmax_level",
     "rf_diag_copy",
     "rf_diag_mfma",
 )
@@ -95,6 +96,8 @@ def load_library():
     lib.rf_moe_routing.argtypes = [P, P, ctypes.c_int, P, P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.rf_fp8_quant_gemm.restype = ctypes.c_int
     lib.rf_fp8_quant_gemm.argtypes = [P, P, P, ctypes.c_void_p]
+    lib.rf_diag_softmax_level.restype = ctypes.c_int
+    lib.rf_diag_softmax_level.argtypes = [P, P, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.rf_diag_mfma.restype = ctypes.c_int
@@ -260,6 +263,16 @@ def rf_fp8_quant_gemm(a, w, c=None, stream=None):
     _check(lib.rf_fp8_quant_gemm(ctypes.byref(da), ctypes.byref(dw), ctypes.byref(dc), _stream(stream)),
            "rf_fp8_quant_gemm")
     return c
+
+
+def rf_diag_softmax_level(x, y, level, ml_buf=None, stream=None):
+    """Softmax with the cascade fused at a chosen level (0 unfused .. 3 per workgroup); study aid."""
+    lib = load_library()
+    dx, dy = tensor_desc(x), tensor_desc(y)
+    p = ctypes.c_void_p(ml_buf.data_ptr()) if ml_buf is not None else None
+    _check(lib.rf_diag_softmax_level(ctypes.byref(dx), ctypes.byref(dy), int(level), p, _stream(stream)),
+           "rf_diag_softmax_level")
+    return y
 
 
 def rf_diag_copy(src, dst, stream=None):

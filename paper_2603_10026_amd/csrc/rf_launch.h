@@ -64,6 +64,12 @@ hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E
 hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, int K, int N,
                                  int64_t lda, int64_t ldw, int64_t ldc, hipStream_t s);
 
+// Fusion-level study of the softmax cascade (bf16 rows, n % 8 == 0, n <= 8192): level 0 =
+// unfused (three kernels; ml_buf holds 2 * rows floats), 1 = fused per lane, 2 = per
+// wavefront (the shipped kernel), 3 = per workgroup.
+hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n, int64_t x_pitch,
+                                int64_t y_pitch, int level, float* ml_buf, hipStream_t s);
+
 // Measurement aids: a plain copy of `bytes` (multiple of 16) and an MFMA-only loop
 // (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
 // workgroups * 256 floats).

@@ -9,9 +9,10 @@
 //
 // Kernel 2 (any row length / alignment): one workgroup streams a row, every
 // lane carrying the level-1 incremental state (m, l) (Appendix A.2,
-// incremental form); lane states are merged with the level-k fused expression
-// (Section 3.2 Eq. (11)) across the wavefront and then across wavefronts
-// through LDS; a second sweep over the row writes the result.
+// incremental form), corrected once per 128-bit vector; lane states are merged
+// with the level-k fused expression (Section 3.2 Eq. (11)) across the wavefront
+// and then across wavefronts through LDS; a second sweep over the row writes
+// the result.
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -20,7 +21,12 @@ namespace rf {
 constexpr int kSoftmaxWavesPerWg = 4;
 
 // One wavefront per row; NCH 128-bit chunks per lane; n % kPerVec == 0.
-template <typename T, int NCH>
+// LANE_LEVEL = false (the shipped path): the two reductions are fused at wavefront level,
+// the row max is known before the sum starts, nothing is ever corrected.
+// LANE_LEVEL = true (fusion-level study only, Section 5.3): every lane runs the level-1
+// incremental form over its own elements, one correction per element, and the 64 lane
+// states are merged with the level-k fused expression.
+template <typename T, int NCH, bool LANE_LEVEL = false>
 __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_regs_kernel(
     const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n, int64_t x_pitch,
     int64_t y_pitch) {
@@ -38,35 +44,65 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_reg
     const int idx = c * kWave + lane;
     if (idx < nvec) raw[c] = __builtin_nontemporal_load(xr + idx);
   }
-  // cascade stage 1: row max
   float m = -INFINITY;
-#pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    if (c * kWave + lane < nvec) {
-      float f[V];
-      Elem<T>::unpack(raw[c], f);
-#pragma unroll
-      for (int i = 0; i < V; ++i) m = fmaxf(m, f[i]);
-    }
-  }
-  m = wave_max(m);
-  // cascade stage 2: sum of exp(x - m), exponentials kept for the epilogue
-  const float mb = -m * kLog2e;
-  float e[NCH][V];
   float l = 0.f;
+  float e[NCH][V];
+  if constexpr (LANE_LEVEL) {
+    // per-lane incremental state, then the merge; exponentials are taken again afterwards
 #pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    if (c * kWave + lane < nvec) {
-      float f[V];
-      Elem<T>::unpack(raw[c], f);
+    for (int c = 0; c < NCH; ++c) {
+      if (c * kWave + lane < nvec) {
+        float f[V];
+        Elem<T>::unpack(raw[c], f);
 #pragma unroll
-      for (int i = 0; i < V; ++i) {
-        e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
-        l += e[c][i];
+        for (int i = 0; i < V; ++i) {
+          const float mn = fmaxf(m, f[i]);
+          l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((f[i] - mn) * kLog2e);
+          m = mn;
+        }
       }
     }
+    const float mw = wave_max(m);
+    l = wave_sum((m == -INFINITY) ? 0.f : l * fast_exp2((m - mw) * kLog2e));
+    m = mw;
+    const float mb = -m * kLog2e;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (c * kWave + lane < nvec) {
+        float f[V];
+        Elem<T>::unpack(raw[c], f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
+      }
+    }
+  } else {
+    // cascade stage 1: row max
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (c * kWave + lane < nvec) {
+        float f[V];
+        Elem<T>::unpack(raw[c], f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) m = fmaxf(m, f[i]);
+      }
+    }
+    m = wave_max(m);
+    // cascade stage 2: sum of exp(x - m), exponentials kept for the epilogue
+    const float mb = -m * kLog2e;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (c * kWave + lane < nvec) {
+        float f[V];
+        Elem<T>::unpack(raw[c], f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
+          l += e[c][i];
+        }
+      }
+    }
+    l = wave_sum(l);
   }
-  l = wave_sum(l);
   const float inv = 1.0f / l;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
@@ -80,24 +116,45 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_reg
   }
 }
 
-// One workgroup per row, any n, scalar accesses; two sweeps over the row.
+// One workgroup per row, any n; two sweeps over the row (the second one is served by the
+// L2 for rows of a few hundred KB).  VEC: rows are 16-byte aligned, so both sweeps use
+// 128-bit accesses and the incremental state is corrected once per vector; otherwise
+// scalar accesses, one correction per element.
 constexpr int kStreamThreads = 256;
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kStreamThreads) void softmax_row_streaming_kernel(
     const T* __restrict__ x, T* __restrict__ y, int64_t rows, int64_t n, int64_t x_pitch,
     int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
   __shared__ float sm[kStreamThreads / kWave];
   __shared__ float sl[kStreamThreads / kWave];
   const int64_t row = blockIdx.x;
   if (row >= rows) return;
   const T* xr = x + row * x_pitch;
   T* yr = y + row * y_pitch;
+  const int64_t nvec = VEC ? n / V : 0;   // full vectors; the rest is handled element-wise
   // level-1 incremental state per lane
   float m = -INFINITY, l = 0.f;
-  for (int64_t j = threadIdx.x; j < n; j += kStreamThreads) {
+  if constexpr (VEC) {
+    const u32x4* xv = reinterpret_cast<const u32x4*>(xr);
+    for (int64_t j = threadIdx.x; j < nvec; j += kStreamThreads) {
+      float f[V];
+      Elem<T>::unpack(xv[j], f);
+      float vm = f[0];
+#pragma unroll
+      for (int i = 1; i < V; ++i) vm = fmaxf(vm, f[i]);
+      const float mn = fmaxf(m, vm);
+      const float mb = -mn * kLog2e;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) sum += fast_exp2(fmaf(f[i], kLog2e, mb));
+      l = l * fast_exp2((m - mn) * kLog2e) + sum;  // exp(m - mn) with m = -inf and l = 0 adds nothing
+      m = mn;
+    }
+  }
+  for (int64_t j = nvec * V + threadIdx.x; j < n; j += kStreamThreads) {
     const float v = Elem<T>::load(xr + j);
     const float mn = fmaxf(m, v);
-    // exp(m - mn) with m = -inf and l = 0 contributes nothing
     l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((v - mn) * kLog2e);
     m = mn;
   }
@@ -117,7 +174,18 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_row_streaming_kernel(
     lg += (sm[w] == -INFINITY) ? 0.f : sl[w] * fast_exp2((sm[w] - mg) * kLog2e);
   const float inv = 1.0f / lg;
   const float mb = -mg * kLog2e;
-  for (int64_t j = threadIdx.x; j < n; j += kStreamThreads) {
+  if constexpr (VEC) {
+    const u32x4* xv = reinterpret_cast<const u32x4*>(xr);
+    u32x4* yv = reinterpret_cast<u32x4*>(yr);
+    for (int64_t j = threadIdx.x; j < nvec; j += kStreamThreads) {
+      float f[V];
+      Elem<T>::unpack(xv[j], f);
+#pragma unroll
+      for (int i = 0; i < V; ++i) f[i] = fast_exp2(fmaf(f[i], kLog2e, mb)) * inv;
+      __builtin_nontemporal_store(Elem<T>::pack(f), yv + j);
+    }
+  }
+  for (int64_t j = nvec * V + threadIdx.x; j < n; j += kStreamThreads) {
     const float v = Elem<T>::load(xr + j);
     Elem<T>::store(yr + j, fast_exp2(fmaf(v, kLog2e, mb)) * inv);
   }
@@ -141,9 +209,87 @@ static hipError_t launch_softmax_t(const T* x, T* y, int64_t rows, int64_t n, in
     else if (nch <= 8) RF_SOFTMAX_CASE(8);
     else RF_SOFTMAX_CASE(16);
 #undef RF_SOFTMAX_CASE
-  } else {
-    hipLaunchKernelGGL((softmax_row_streaming_kernel<T>), dim3((unsigned)rows),
+  } else if (vec_ok) {
+    hipLaunchKernelGGL((softmax_row_streaming_kernel<T, true>), dim3((unsigned)rows),
                        dim3(kStreamThreads), 0, s, x, y, rows, n, x_pitch, y_pitch);
+  } else {
+    hipLaunchKernelGGL((softmax_row_streaming_kernel<T, false>), dim3((unsigned)rows),
+                       dim3(kStreamThreads), 0, s, x, y, rows, n, x_pitch, y_pitch);
+  }
+  return hipGetLastError();
+}
+
+// ---- fusion-level study (Section 5.3): the unfused chain as three kernels ----
+// One wavefront per row, 128-bit loads; m and l pass through memory between the kernels.
+// PASS 0: m = max x;  PASS 1: l = sum exp(x - m);  PASS 2: y = exp(x - m) / l.
+template <typename T, int PASS>
+__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_unfused_pass_kernel(
+    const T* __restrict__ x, T* __restrict__ y, float* __restrict__ m_buf, float* __restrict__ l_buf,
+    int64_t rows, int n, int64_t x_pitch, int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t row = (int64_t)blockIdx.x * kSoftmaxWavesPerWg + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const u32x4* xr = reinterpret_cast<const u32x4*>(x + row * x_pitch);
+  u32x4* yr = reinterpret_cast<u32x4*>(y + row * y_pitch);
+  const int nvec = n / V;
+  float acc = PASS == 0 ? -INFINITY : 0.f;
+  const float mb = PASS == 0 ? 0.f : -m_buf[row] * kLog2e;
+  const float inv = PASS == 2 ? 1.0f / l_buf[row] : 0.f;
+  for (int idx = lane; idx < nvec; idx += kWave) {
+    float f[V];
+    Elem<T>::unpack(xr[idx], f);
+    if constexpr (PASS == 0) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc = fmaxf(acc, f[i]);
+    } else if constexpr (PASS == 1) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc += fast_exp2(fmaf(f[i], kLog2e, mb));
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i) f[i] = fast_exp2(fmaf(f[i], kLog2e, mb)) * inv;
+      yr[idx] = Elem<T>::pack(f);
+    }
+  }
+  if constexpr (PASS == 0) { acc = wave_max(acc); if (lane == 0) m_buf[row] = acc; }
+  if constexpr (PASS == 1) { acc = wave_sum(acc); if (lane == 0) l_buf[row] = acc; }
+}
+
+// level 0: unfused (three kernels, needs ml_buf = 2 * rows floats); 1: fused per lane;
+// 2: fused per wavefront (the shipped kernel); 3: fused per workgroup (the streaming kernel).
+// bf16 only, n a multiple of 8 and at most 8192, 16-byte aligned rows.
+hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n, int64_t x_pitch,
+                                int64_t y_pitch, int level, float* ml_buf, hipStream_t s) {
+  typedef bf16_t T;
+  const T* xp = (const T*)x;
+  T* yp = (T*)y;
+  const int64_t per_chunk = (int64_t)Elem<T>::kPerVec * kWave;
+  if (n % Elem<T>::kPerVec != 0 || n > 16 * per_chunk || level < 0 || level > 3) return hipErrorInvalidValue;
+  const unsigned grid = (unsigned)((rows + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg);
+  const dim3 block(kSoftmaxWavesPerWg * kWave);
+  if (level == 0) {
+    if (ml_buf == nullptr) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((softmax_unfused_pass_kernel<T, 0>), dim3(grid), block, 0, s, xp, yp, ml_buf, ml_buf + rows, rows, (int)n, x_pitch, y_pitch);
+    hipLaunchKernelGGL((softmax_unfused_pass_kernel<T, 1>), dim3(grid), block, 0, s, xp, yp, ml_buf, ml_buf + rows, rows, (int)n, x_pitch, y_pitch);
+    hipLaunchKernelGGL((softmax_unfused_pass_kernel<T, 2>), dim3(grid), block, 0, s, xp, yp, ml_buf, ml_buf + rows, rows, (int)n, x_pitch, y_pitch);
+  } else if (level == 1 || level == 2) {
+    const int nch = (int)((n + per_chunk - 1) / per_chunk);
+#define RF_SOFTMAX_LEVEL_CASE(N)                                                                    \
+  if (level == 1)                                                                                   \
+    hipLaunchKernelGGL((softmax_row_in_regs_kernel<T, N, true>), dim3(grid), block, 0, s, xp, yp,   \
+                       rows, (int)n, x_pitch, y_pitch);                                             \
+  else                                                                                              \
+    hipLaunchKernelGGL((softmax_row_in_regs_kernel<T, N, false>), dim3(grid), block, 0, s, xp, yp,  \
+                       rows, (int)n, x_pitch, y_pitch)
+    if (nch <= 1) { RF_SOFTMAX_LEVEL_CASE(1); }
+    else if (nch <= 2) { RF_SOFTMAX_LEVEL_CASE(2); }
+    else if (nch <= 4) { RF_SOFTMAX_LEVEL_CASE(4); }
+    else if (nch <= 8) { RF_SOFTMAX_LEVEL_CASE(8); }
+    else { RF_SOFTMAX_LEVEL_CASE(16); }
+#undef RF_SOFTMAX_LEVEL_CASE
+  } else {
+    hipLaunchKernelGGL((softmax_row_streaming_kernel<T, true>), dim3((unsigned)rows), dim3(kStreamThreads), 0, s,
+                       xp, yp, rows, n, x_pitch, y_pitch);
   }
   return hipGetLastError();
 }

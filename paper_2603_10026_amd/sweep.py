@@ -1,9 +1,15 @@
-"""Split-count sweep for multi-segment attention (paper Section 5.4.2: the effect of the number
-of segments on a long-sequence decode).  Times rf_cascade_attention_splitk + rf_merge_states on
-the decode benchmark workload for several segment counts S and prints one line per S; the
-fastest S is the value to pass as ``num_splits`` on this GPU.
+"""Two sweeps that reproduce the paper's ablations on this GPU.
 
-    python -m paper_2603_10026_amd.sweep [--splits 8,16,32,64,128,256] [--iters 20]
+``--what splits`` (default): split-count sweep for multi-segment attention (the effect of the
+number of segments on a long-sequence decode).  Times rf_cascade_attention_splitk +
+rf_merge_states on the decode benchmark workload for several segment counts S and prints one
+line per S; the fastest S is the value to pass as ``num_splits`` on this GPU.
+
+``--what fusion``: the safe-softmax cascade fused at different levels (not fused / per lane /
+per wavefront / per workgroup) for row lengths 1K..8K, 32768 rows of bf16, through
+rf_diag_softmax_level.
+
+    python -m paper_2603_10026_amd.sweep [--what splits|fusion] [--splits 8,16,...] [--iters 20]
 """
 import argparse
 import json
@@ -14,7 +20,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--splits", type=str, default="8,16,32,64,128,256,512")
     ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--what", type=str, default="splits", choices=["splits", "fusion"])
     args = ap.parse_args()
+    if args.what == "fusion":
+        return fusion_sweep(args.iters)
     import torch
     from . import binding as rf
     from . import inputs as I
@@ -58,6 +67,40 @@ def main():
         del parts, outs
     best = min(rows, key=lambda r: r["us_median"])
     print(json.dumps(dict(best_num_splits=best["num_splits"], us_median=best["us_median"])), flush=True)
+
+
+def fusion_sweep(iters):
+    import torch
+    from . import binding as rf
+    from . import inputs as I
+
+    rf.load_library()
+    dev = "cuda:0"
+    rows, n_rot = 32768, 3
+    names = {0: "not fused (3 kernels)", 1: "fused per lane", 2: "fused per wavefront", 3: "fused per workgroup"}
+    for n in (1024, 2048, 4096, 8192):
+        xs = [I.softmax_inputs_device(I.SEED_BASE + 1 + 100 * r, rows, n, 2.0, "bf16", dev) for r in range(n_rot)]
+        ys = [torch.empty_like(x) for x in xs]
+        ml = torch.empty(2 * rows, dtype=torch.float32, device=dev)
+        base = None
+        for level in (0, 1, 2, 3):
+            for i in range(3):
+                rf.rf_diag_softmax_level(xs[i % n_rot], ys[i % n_rot], level, ml)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+            for i in range(iters):
+                evs[i][0].record()
+                rf.rf_diag_softmax_level(xs[i % n_rot], ys[i % n_rot], level, ml)
+                evs[i][1].record()
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            med = ts[len(ts) // 2]
+            base = med if level == 0 else base
+            print(json.dumps(dict(n=n, level=level, fusion=names[level], us_median=round(med, 1),
+                                  GBps=round(4.0 * rows * n / med / 1e3, 1),
+                                  speedup_over_unfused=round(base / med, 2))), flush=True)
+        del xs, ys
+    return 0
 
 
 if __name__ == "__main__":

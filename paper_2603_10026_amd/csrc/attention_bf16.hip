@@ -2,7 +2,7 @@
 // A.2 incremental forms; Appendix A.4 tile-level structure), bf16 MFMA
 // 32x32x16 with fp32 accumulation.
 //
-// One workgroup (4 wavefronts) owns 128 query rows of one (batch, head); each
+// One workgroup (4 or 8 wavefronts) owns 128 or 256 query rows of one (batch, head); each
 // wavefront owns 32 of them as the N dimension of its MFMA tiles and streams
 // the keys in tiles of 64, carrying the running state (m, l, acc) of the
 // max -> sum-exp -> weighted-sum cascade.  acc stays unnormalised (Eq. (8))
@@ -37,9 +37,8 @@ namespace rf {
 
 namespace {
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * kWave;
-constexpr int kBQ = 128;  // query rows per workgroup
+// NW wavefronts of 32 query rows each per workgroup: 4 (two workgroups per CU) or 8 (one
+// workgroup per CU; half the K/V loads and LDS traffic per MFMA)
 constexpr int kBK = 64;   // keys per tile
 constexpr float kTau = 8.0f;
 
@@ -65,8 +64,8 @@ __device__ __forceinline__ void wait_vmem_all() {
 
 }  // namespace
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
+template <int D, int NW>
+__global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     bf16_t* __restrict__ o, Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so, int Hq, int Hkv,
     int Lq, int Lk, float scale_log2e, int causal, int n_qtiles) {
@@ -76,6 +75,8 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
   constexpr int ROWB = D * 2;                // bytes per K/V row
   constexpr int TILEB = kBK * ROWB;          // bytes per K or V tile
   constexpr int ROWS_PER_LD = 1024 / ROWB;   // rows covered by one wavefront load
+  constexpr int kWaves = NW;
+  constexpr int kBQ = 32 * NW;               // query rows per workgroup
   constexpr int LD_PER_WAVE = kBK / ROWS_PER_LD / kWaves;
 
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * TILEB];  // [buf][K,V]
@@ -261,7 +262,8 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
     // The loads of the next tile are issued one at a time between the MFMAs.  Issued in a
     // burst right after the barrier, the eight wavefronts of a CU queue up behind each
     // other in the vector-memory unit and every one of them idles for the whole burst.
-    static_assert(2 * LD_PER_WAVE == KS, "one load per contraction step");
+    constexpr int kIssueEvery = KS / (2 * LD_PER_WAVE);  // contraction steps per load
+    static_assert(kIssueEvery * 2 * LD_PER_WAVE == KS, "loads spread evenly over the contraction steps");
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
@@ -269,7 +271,8 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
         s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk][rt]),
                                                         __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
                                                         0, 0, 0);
-      if (more) issue_one(key0 + kBK, BUF ^ 1, kk >> 1, kk & 1);
+      if (more && kk % kIssueEvery == 0)
+        issue_one(key0 + kBK, BUF ^ 1, (kk / kIssueEvery) >> 1, (kk / kIssueEvery) & 1);
       __builtin_amdgcn_sched_barrier(0);
     }
     // ---- V^T fragments of the first two contraction steps: requested now, they arrive
@@ -400,21 +403,26 @@ __global__ __launch_bounds__(kThreads, 2) void attention_bf16_kernel(
 hipError_t launch_attention_bf16(const void* q, const void* k, const void* v, void* o, Strides4 sq,
                                  Strides4 sk, Strides4 sv, Strides4 so, const AttnShape& a,
                                  hipStream_t s) {
-  const int n_qtiles = (a.Lq + kBQ - 1) / kBQ;
+  // Without a mask the larger workgroup wins (fewer loads per MFMA); under a causal mask the
+  // smaller one does (finer tiles balance better and waste less on the diagonal).
+  const int nw = (a.causal || a.Lq <= 128) ? 4 : 8;
+  const int bq = 32 * nw;
+  const int n_qtiles = (a.Lq + bq - 1) / bq;
   const int64_t grid = (int64_t)n_qtiles * a.B * a.Hq;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
   const float sl2 = a.scale * kLog2e;
+#define RF_LAUNCH_ATTN(DD, NWW)                                                                   \
+  hipLaunchKernelGGL((attention_bf16_kernel<DD, NWW>), dim3((unsigned)grid), dim3(NWW * kWave), 0, s, \
+                     (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, sq, sk, sv, so, \
+                     a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal, n_qtiles)
   if (a.d == 128) {
-    hipLaunchKernelGGL((attention_bf16_kernel<128>), dim3((unsigned)grid), dim3(kThreads), 0, s,
-                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, sq, sk, sv,
-                       so, a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal, n_qtiles);
+    if (nw == 4) RF_LAUNCH_ATTN(128, 4); else RF_LAUNCH_ATTN(128, 8);
   } else if (a.d == 64) {
-    hipLaunchKernelGGL((attention_bf16_kernel<64>), dim3((unsigned)grid), dim3(kThreads), 0, s,
-                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, sq, sk, sv,
-                       so, a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal, n_qtiles);
+    if (nw == 4) RF_LAUNCH_ATTN(64, 4); else RF_LAUNCH_ATTN(64, 8);
   } else {
     return hipErrorInvalidValue;
   }
+#undef RF_LAUNCH_ATTN
   return hipGetLastError();
 }
 

@@ -373,7 +373,11 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
 #undef RF_FENCE
     wslot = wslot == 0 ? 2 : wslot - 1;  // (wslot + 2) % 3
   }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  // (the registers of the surplus prefetch stay reserved until it has landed)
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"
+               : "+v"(xreg[0]), "+v"(xreg[1]), "+v"(xreg[2]), "+v"(xreg[3])
+               :
+               : "memory");
 #undef RF_ISSUE_W
 #undef RF_LOAD_X
 #undef RF_WAIT_X2

@@ -298,7 +298,11 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
     if (s + 1 < nk) k_step(s + 1, std::integral_constant<int, 1>{});
   }
   ss = ss_done;
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  // (the registers of the surplus prefetch stay reserved until it has landed)
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"
+               : "+v"(xreg[0]), "+v"(xreg[1]), "+v"(greg[0]), "+v"(greg[1])
+               :
+               : "memory");
 #undef RF_LOAD_PIECE
 #undef RF_ISSUE_W
 #undef RF_WAIT_PIECE

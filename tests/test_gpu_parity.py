@@ -135,6 +135,8 @@ ATTN_CASES = [
     ("bf16", 1, 2, 2, 200, 200, 64, False),
     ("bf16", 1, 2, 1, 200, 260, 64, True),
     ("bf16", 1, 1, 1, 384, 1024, 128, True),
+    ("bf16", 1, 2, 1, 300, 450, 128, False),    # 256-query workgroups, ragged second tile
+    ("bf16", 2, 2, 2, 513, 129, 64, False),     # 256-query workgroups, one-row tail tile
 ]
 
 

@@ -40,7 +40,14 @@ constexpr int kQLdsB = kQCorrBase + 2 * kQM * 4 + kQM * 4;  // + 2 stages of fac
 constexpr float kE4M3Max = 448.0f;
 
 // 16-byte slot swizzles
-__device__ __forceinline__ int fQX(int row) { return (row >> 1) & 7; }  // 8 slots per token row
+// 8 slots per token row.  Bits of the row are mixed so that both access shapes are free of
+// bank conflicts: the 64-bit quantised stores (4 lanes per row, consecutive rows) need rows
+// r..r+3 to differ in the upper slot bits, the 128-bit fragment reads (one row per lane)
+// need 8 distinct values over the rows of equal parity.
+__device__ __forceinline__ int fQX(int row) {
+  const int b0 = row & 1, b1 = (row >> 1) & 1, b2 = (row >> 2) & 1, b3 = (row >> 3) & 1;
+  return (b1 << 2) | ((b0 ^ b2) << 1) | b3;
+}
 __device__ __forceinline__ int fQW(int row) { return (row >> 2) & 3; }  // 4 slots per weight row
 
 }  // namespace

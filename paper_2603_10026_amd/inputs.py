@@ -37,6 +37,37 @@ WORKLOADS = {
             M=4096, K=4096, N=4096, eps=1e-6, w_sigma=0.02),
 }
 
+# Shapes of the paper's appendix tables for the further cascades.
+MOE_ROUTING_TABLE = {   # name: (s, hd, en, topk)
+    "R1": (2048, 768, 128, 1), "R2": (2048, 1024, 128, 1), "R3": (2048, 4096, 128, 1), "R4": (2048, 2560, 64, 6),
+    "R5": (2048, 8192, 64, 8), "R6": (2048, 2048, 64, 6), "R7": (2048, 2048, 128, 8), "R8": (2048, 4096, 128, 8),
+}
+FP8_QUANT_GEMM_TABLE = {   # name: (M, N, K)
+    "Q1": (4096, 1536, 2560), "Q2": (4096, 2560, 1536), "Q3": (4096, 3584, 8192), "Q4": (4096, 8192, 3584),
+    "Q5": (4096, 7168, 2048), "Q6": (4096, 2048, 7168), "Q7": (4096, 2048, 768), "Q8": (4096, 768, 2048),
+    "Q9": (4096, 4096, 1536), "Q10": (4096, 1536, 4096),
+}
+VARIANCE_TABLE = {   # name: (bs, l)
+    "V1": (1, 8192), "V2": (1, 32768), "V3": (128, 8192), "V4": (128, 32768),
+    "V5": (512, 8192), "V6": (512, 32768), "V7": (1024, 8192), "V8": (1024, 32768),
+}
+
+
+def table_workload(key):
+    """Workload description (same fields as EXTRA_WORKLOADS) of one row of the tables above."""
+    if key in MOE_ROUTING_TABLE:
+        s, hd, en, topk = MOE_ROUTING_TABLE[key]
+        return dict(name=f"moe_routing_bf16_s{s}_hd{hd}_en{en}_top{topk}", kind="moe_routing", dtype="bf16",
+                    S=s, hd=hd, E=en, topk=topk, score_sigma=1.5)
+    if key in FP8_QUANT_GEMM_TABLE:
+        m, n, k = FP8_QUANT_GEMM_TABLE[key]
+        return dict(name=f"fp8_quant_gemm_m{m}_n{n}_k{k}", kind="fp8_quant_gemm", dtype="fp8", M=m, N=n, K=k)
+    if key in VARIANCE_TABLE:
+        bs, l = VARIANCE_TABLE[key]
+        return dict(name=f"variance_f32_{bs}x{l}", kind="variance", dtype="f32", bs=bs, l=l, mu=1.0, sigma=2.0)
+    raise KeyError(key)
+
+
 # Workloads of the paper's further cascades (its appendix tables), largest configurations.
 EXTRA_WORKLOADS = {
     "moe_routing_r5": dict(name="moe_routing_bf16_s2048_hd8192_en64_top8", kind="moe_routing", dtype="bf16",

@@ -9,7 +9,10 @@ line per S; the fastest S is the value to pass as ``num_splits`` on this GPU.
 per wavefront / per workgroup) for row lengths 1K..8K, 32768 rows of bf16, through
 rf_diag_softmax_level.
 
-    python -m paper_2603_10026_amd.sweep [--what splits|fusion] [--splits 8,16,...] [--iters 20]
+``--what tables``: every shape of the paper's appendix tables for the further cascades (MoE
+routing R1-R8, FP8 quant + GEMM Q1-Q10, variance V1-V8), one JSON line each.
+
+    python -m paper_2603_10026_amd.sweep [--what splits|fusion|tables] [--splits 8,16,...] [--iters 20]
 """
 import argparse
 import json
@@ -20,10 +23,12 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--splits", type=str, default="8,16,32,64,128,256,512")
     ap.add_argument("--iters", type=int, default=20)
-    ap.add_argument("--what", type=str, default="splits", choices=["splits", "fusion"])
+    ap.add_argument("--what", type=str, default="splits", choices=["splits", "fusion", "tables"])
     args = ap.parse_args()
     if args.what == "fusion":
         return fusion_sweep(args.iters)
+    if args.what == "tables":
+        return tables_sweep(args.iters)
     import torch
     from . import binding as rf
     from . import inputs as I
@@ -100,6 +105,65 @@ def fusion_sweep(iters):
                                   GBps=round(4.0 * rows * n / med / 1e3, 1),
                                   speedup_over_unfused=round(base / med, 2))), flush=True)
         del xs, ys
+    return 0
+
+
+def tables_sweep(iters):
+    import torch
+    from . import binding as rf
+    from . import inputs as I
+
+    rf.load_library()
+    dev = "cuda:0"
+    n_rot = 3
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for i in range(iters):
+            evs[i][0].record()
+            fn(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return ts[len(ts) // 2]
+
+    for key in sorted(I.MOE_ROUTING_TABLE):
+        c = I.table_workload(key)
+        sets = []
+        for r in range(n_rot):
+            x, w = I.moe_routing_inputs_device(I.SEED_BASE + 5 + 100 * r, c["S"], c["hd"], c["E"], c["score_sigma"], "bf16", dev)
+            sets.append((x, w, torch.empty((c["S"], c["topk"]), dtype=torch.float32, device=dev),
+                         torch.empty((c["S"], c["topk"]), dtype=torch.int32, device=dev)))
+        ws = torch.empty(rf.moe_routing_workspace_bytes(c["S"], c["hd"], c["E"]), dtype=torch.uint8, device=dev)
+        med = timed(lambda i: rf.rf_moe_routing(sets[i % n_rot][0], sets[i % n_rot][1], c["topk"], prob=sets[i % n_rot][2],
+                                                idx=sets[i % n_rot][3], workspace=ws))
+        b = 2.0 * c["S"] * c["hd"] + 2.0 * c["hd"] * c["E"] + 8.0 * c["S"] * c["topk"]
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), algorithmic_MB=round(b / 1e6, 2),
+                              GBps=round(b / med / 1e3, 1))), flush=True)
+        del sets, ws
+    for key in sorted(I.FP8_QUANT_GEMM_TABLE, key=lambda k: int(k[1:])):
+        c = I.table_workload(key)
+        a, w = I.fp8_quant_gemm_inputs_device(I.SEED_BASE + 7, c["M"], c["K"], c["N"], dev)
+        out = torch.empty((c["M"], c["N"]), dtype=torch.bfloat16, device=dev)
+        med = timed(lambda i: rf.rf_fp8_quant_gemm(a, w, c=out))
+        fl = 2.0 * c["M"] * c["K"] * c["N"]
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), GFLOP=round(fl / 1e9, 1),
+                              TFLOPs=round(fl / med / 1e6, 1))), flush=True)
+        del a, w, out
+    for key in sorted(I.VARIANCE_TABLE, key=lambda k: int(k[1:])):
+        c = I.table_workload(key)
+        xs = [I.variance_inputs_device(I.SEED_BASE + 6 + 100 * r, c["bs"], c["l"], c["dtype"], c["mu"], c["sigma"], dev)
+              for r in range(n_rot)]
+        mv = [(torch.empty(c["bs"], dtype=torch.float32, device=dev), torch.empty(c["bs"], dtype=torch.float32, device=dev))
+              for _ in range(n_rot)]
+        med = timed(lambda i: rf.rf_variance(xs[i % n_rot], *mv[i % n_rot]))
+        b = 4.0 * c["bs"] * c["l"] + 8.0 * c["bs"]
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), algorithmic_MB=round(b / 1e6, 2),
+                              GBps=round(b / med / 1e3, 1))), flush=True)
+        del xs, mv
     return 0
 
 

@@ -201,3 +201,23 @@ def test_binding_descriptor_from_torch_tensor():
     assert d.dtype == B.RF_BF16 and d.data == t.data_ptr()
     with pytest.raises(TypeError):
         B.tensor_desc(torch.zeros(4, dtype=torch.float16))
+
+
+def test_tensor_descriptor_fields():
+    """The packed descriptor carries pointer, dtype, rank, shape and element strides field by field."""
+    import ctypes
+    import torch
+    from paper_2603_10026_amd import binding as B
+    t = torch.empty(2, 3, 4, 5, 6, dtype=torch.bfloat16).permute(0, 2, 1, 3, 4)
+    d = B.tensor_desc(t)
+    assert ctypes.sizeof(d) == 96
+    assert d.data == t.data_ptr() and d.dtype == B.RF_BF16 and d.ndim == 5
+    assert list(d.shape) == [2, 4, 3, 5, 6] and list(d.stride) == list(t.stride())
+    d = B.tensor_desc(torch.empty(7, dtype=torch.int32))
+    assert d.dtype == B.RF_I32 and d.ndim == 1 and list(d.shape) == [7, 0, 0, 0, 0] and list(d.stride) == [1, 0, 0, 0, 0]
+    d = B.tensor_desc(torch.empty(0, 4))
+    assert d.data is None and d.dtype == B.RF_F32 and list(d.shape)[:2] == [0, 4]
+    with pytest.raises(TypeError):
+        B.tensor_desc(torch.empty(3, dtype=torch.float64))
+    with pytest.raises(ValueError):
+        B.tensor_desc(torch.empty(1, 1, 1, 1, 1, 1))

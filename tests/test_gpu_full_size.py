@@ -154,9 +154,10 @@ def test_workload4_rmsnorm_gemm_full(rf):
     check_rows(I.to_numpy(y[idx]), ref, 2e-2, "rmsnorm_gemm rows", row_tol=2e-2)
 
 
-def test_variance_full(rf):
-    c = I.EXTRA_WORKLOADS["variance_v8"]
-    say(c["name"])
+@pytest.mark.parametrize("key", sorted(I.VARIANCE_TABLE, key=lambda k: int(k[1:])))
+def test_variance_full(rf, key):
+    c = I.table_workload(key)
+    say(f"{key} {c['name']}")
     x = I.variance_inputs_device(I.SEED_BASE + 6, c["bs"], c["l"], c["dtype"], c["mu"], c["sigma"], DEV)
     mean, var = rf.rf_variance(x)
     torch.cuda.synchronize()
@@ -165,10 +166,10 @@ def test_variance_full(rf):
     check_rows(I.to_numpy(var)[:, None], v_ref[:, None], 1e-5, "variance var", row_tol=1e-5)
 
 
-@pytest.mark.parametrize("key", ["moe_routing_r5", "moe_routing_r8"])
+@pytest.mark.parametrize("key", sorted(I.MOE_ROUTING_TABLE))
 def test_moe_routing_full(rf, key):
-    c = I.EXTRA_WORKLOADS[key]
-    say(c["name"])
+    c = I.table_workload(key)
+    say(f"{key} {c['name']}")
     x, w = I.moe_routing_inputs_device(I.SEED_BASE + 5, c["S"], c["hd"], c["E"], c["score_sigma"], "bf16", DEV)
     prob, idx = rf.rf_moe_routing(x, w, c["topk"])
     torch.cuda.synchronize()
@@ -191,10 +192,10 @@ def test_moe_routing_full(rf, key):
     assert float(np.max(np.abs(np.sort(prob, axis=1) - np.sort(p_ref, axis=1)))) <= 1e-5 * float(np.max(p_ref)) + 1e-7
 
 
-@pytest.mark.parametrize("key", ["fp8_quant_gemm_q3", "fp8_quant_gemm_q4"])
+@pytest.mark.parametrize("key", sorted(I.FP8_QUANT_GEMM_TABLE, key=lambda k: int(k[1:])))
 def test_fp8_quant_gemm_full(rf, key):
-    c = I.EXTRA_WORKLOADS[key]
-    say(c["name"])
+    c = I.table_workload(key)
+    say(f"{key} {c['name']}")
     a, w = I.fp8_quant_gemm_inputs_device(I.SEED_BASE + 7, c["M"], c["K"], c["N"], DEV)
     out = rf.rf_fp8_quant_gemm(a, w)
     torch.cuda.synchronize()

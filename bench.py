@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--only", type=str, default="",
                     help="comma list of w0..w4 and x1.. (profiling aid); default all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 256 MiB -> 256 MiB copy kernel before the warmup "
                          "(reference dispatch for scaling the FETCH_SIZE / WRITE_SIZE counters)")
@@ -158,6 +159,31 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # The same steps captured once in a HIP graph and replayed: what a serving loop that cannot
+    # afford per-launch host work would run.  Reported next to, never instead of, ms_per_step.
+    graph_replay = None
+    if not args.no_graph and launches:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for i in range(N_ROT):
+                run_step(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // N_ROT)
+        g0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        graph_replay = dict(ms_per_step=round((g1 - g0) * 1e3 / (reps * N_ROT), 4), steps_per_graph=N_ROT, replays=reps)
+        del graph
 
     # average kernel duration per launch over the timed region (HIP events on the launch stream)
     dur_us = {}
@@ -384,6 +410,7 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]} if dominant else None,
         "rooflines": rooflines,
         "ceilings": ceilings,
+        "graph_replay": graph_replay,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

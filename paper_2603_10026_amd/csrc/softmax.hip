@@ -13,6 +13,8 @@
 // with the level-k fused expression (Section 3.2 Eq. (11)) across the wavefront
 // and then across wavefronts through LDS; a second sweep over the row writes
 // the result.
+#include <type_traits>
+
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -26,8 +28,17 @@ constexpr int kSoftmaxWavesPerWg = 4;
 // LANE_LEVEL = true (fusion-level study only, Section 5.3): every lane runs the level-1
 // incremental form over its own elements, one correction per element, and the 64 lane
 // states are merged with the level-k fused expression.
+// Wavefronts per SIMD the register allocator has to leave room for, by the number of fp32 values
+// a lane holds: without the bound the scheduler spends registers on instruction-level
+// parallelism this HBM-bound kernel has no use for, and occupancy (bytes in flight) drops.
+constexpr int softmax_waves_per_simd(int floats_per_lane) {
+  return floats_per_lane <= 32 ? 8 : floats_per_lane <= 64 ? 4 : 2;
+}
+
 template <typename T, int NCH, bool LANE_LEVEL = false>
-__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_regs_kernel(
+__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave,
+                             softmax_waves_per_simd(NCH * Elem<T>::kPerVec) * 4 / kSoftmaxWavesPerWg)
+void softmax_row_in_regs_kernel(
     const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n, int64_t x_pitch,
     int64_t y_pitch) {
   constexpr int V = Elem<T>::kPerVec;
@@ -38,26 +49,37 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_reg
   u32x4* yr = reinterpret_cast<u32x4*>(y + row * y_pitch);
   const int nvec = n / V;
 
-  u32x4 raw[NCH];
+  // Straight-line code: vectors past the end of the row are loaded from the last valid
+  // vector and replaced by -inf (the identity of the max stage; exp gives 0 for the sum
+  // stage), so no stage below needs a branch.  Only the stores are predicated.
+  // The row lives in registers as fp32 from here on: e[][] holds x, then exp(x - m).
+  constexpr uint32_t kNegInf = std::is_same<T, float>::value ? 0xFF800000u : 0xFF80FF80u;
+  // Full vectors sit at one lane address plus a constant; the vector that holds the end of the
+  // row (and any vector past it) is read at a clamped address of its own.
+  const u32x4* xl = xr + lane;
+  const u32x4* xt = xr + min((nvec - 1) / kWave * kWave + lane, nvec - 1);
+  float e[NCH][V];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int idx = c * kWave + lane;
-    if (idx < nvec) raw[c] = __builtin_nontemporal_load(xr + idx);
+    const bool full = (c + 1) * kWave <= nvec;  // wave-uniform
+    u32x4 r = __builtin_nontemporal_load(full ? xl + c * kWave : xt);
+    const bool ok = idx < nvec;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = ok ? r[j] : kNegInf;
+    Elem<T>::unpack(r, e[c]);
   }
   float m = -INFINITY;
   float l = 0.f;
-  float e[NCH][V];
   if constexpr (LANE_LEVEL) {
     // per-lane incremental state, then the merge; exponentials are taken again afterwards
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       if (c * kWave + lane < nvec) {
-        float f[V];
-        Elem<T>::unpack(raw[c], f);
 #pragma unroll
         for (int i = 0; i < V; ++i) {
-          const float mn = fmaxf(m, f[i]);
-          l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((f[i] - mn) * kLog2e);
+          const float mn = fmaxf(m, e[c][i]);
+          l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((e[c][i] - mn) * kLog2e);
           m = mn;
         }
       }
@@ -67,39 +89,26 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_row_in_reg
     m = mw;
     const float mb = -m * kLog2e;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      if (c * kWave + lane < nvec) {
-        float f[V];
-        Elem<T>::unpack(raw[c], f);
+    for (int c = 0; c < NCH; ++c)
 #pragma unroll
-        for (int i = 0; i < V; ++i) e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
-      }
-    }
+      for (int i = 0; i < V; ++i) e[c][i] = fast_exp2(fmaf(e[c][i], kLog2e, mb));
   } else {
     // cascade stage 1: row max
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      if (c * kWave + lane < nvec) {
-        float f[V];
-        Elem<T>::unpack(raw[c], f);
+    for (int c = 0; c < NCH; ++c)
 #pragma unroll
-        for (int i = 0; i < V; ++i) m = fmaxf(m, f[i]);
-      }
-    }
+      for (int i = 0; i < V; ++i) m = fmaxf(m, e[c][i]);
     m = wave_max(m);
     // cascade stage 2: sum of exp(x - m), exponentials kept for the epilogue
     const float mb = -m * kLog2e;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      if (c * kWave + lane < nvec) {
-        float f[V];
-        Elem<T>::unpack(raw[c], f);
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-          e[c][i] = fast_exp2(fmaf(f[i], kLog2e, mb));
-          l += e[c][i];
-        }
+      for (int i = 0; i < V; ++i) {
+        e[c][i] = fast_exp2(fmaf(e[c][i], kLog2e, mb));
+        l += e[c][i];
       }
+      __builtin_amdgcn_sched_barrier(0);  // one vector at a time: no extra live temporaries
     }
     l = wave_sum(l);
   }

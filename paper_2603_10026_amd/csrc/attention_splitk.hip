@@ -10,7 +10,8 @@
 // the four states are merged through LDS with the level-k fused expression
 // (Section 3.2 Eq. (11)) and the chunk's UNNORMALISED state is written out.
 //
-// Data movement.  K: coalesced 128-bit global loads -> wavefront-private,
+// Data movement (K and V are read once: non-temporal loads, which stream measurably
+// faster than cached ones).  K: coalesced 128-bit global loads -> wavefront-private,
 // XOR-swizzled LDS tile -> 128-bit LDS reads in MFMA A-operand layout.
 // V: 128-bit global loads of whole rows straight into registers, followed by
 // an 8x8 16-bit register transpose that yields the A operand of
@@ -41,7 +42,7 @@ __device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
 
 // Two workgroups per compute unit: bounding the registers for three was measured 1.4 % slower
 // (back-to-back launches, same process) although it hides a workgroup's prologue and epilogue.
-__global__ __launch_bounds__(kSplitWaves * kWave) void attention_splitk_bf16_kernel(
+__global__ __launch_bounds__(kSplitWaves * kWave, 2) void attention_splitk_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     Strides4 sq, Strides4 sk, Strides4 sv, float* __restrict__ part_m,
     float* __restrict__ part_l, float* __restrict__ part_acc, int Hq, int Hkv, int Lq, int Lk,
@@ -94,23 +95,50 @@ __global__ __launch_bounds__(kSplitWaves * kWave) void attention_splitk_bf16_ker
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int key0 = lo + wave * kTileKeys; key0 < hi; key0 += kSplitWaves * kTileKeys) {
-      // ---- K tile: global -> LDS (swizzled) ----
-      u32x4 kreg[8];
+    // K of a step is fetched one step ahead (two register sets) and V at the start of its
+    // step: K is needed first (it goes through LDS before the first MFMA), V only after the
+    // scores and the softmax, which cover its latency.  Two full sets do not fit the registers.
+    // slot e of kreg: key row 4e + g; slot e of vreg: key 4g + e (e < 4), 16 + 4g + (e - 4).
+    // Full tiles: wave-uniform tile base (scalar registers) + loop-invariant 32-bit lane offsets.
+    uint32_t koff[8], voff[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = 4 * e + g;  // 0..31
-        const int key = min(key0 + row, Lk - 1);
-        kreg[e] = *reinterpret_cast<const u32x4*>(kb + (int64_t)key * sk.l + 8 * i16);
-      }
-      // ---- V rows: global -> registers.  slot e<4: key 4g+e; e>=4: key 16+4g+(e-4)
-      u32x4 vreg[8];
+    for (int e = 0; e < 8; ++e) {
+      koff[e] = (uint32_t)(((int64_t)(4 * e + g) * sk.l + 8 * i16) * 2);
+      voff[e] = (uint32_t)(((int64_t)((e < 4) ? (4 * g + e) : (16 + 4 * g + (e - 4))) * sv.l + 8 * i16) * 2);
+    }
+    const bool small_stride = sk.l < (1 << 24) && sv.l < (1 << 24);  // offsets fit 32 bits
+    auto issue_k = [&](int key0_, u32x4 (&kreg)[8]) {
+      const int key0 = __builtin_amdgcn_readfirstlane(key0_);
+      if (key0 + kTileKeys <= Lk && small_stride) {
+        const char* kt = reinterpret_cast<const char*>(kb) + (int64_t)key0 * sk.l * 2;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = (e < 4) ? (4 * g + e) : (16 + 4 * g + (e - 4));
-        const int key = min(key0 + row, Lk - 1);
-        vreg[e] = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * sv.l + 8 * i16);
+        for (int e = 0; e < 8; ++e)
+          kreg[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kt + koff[e]));
+      } else {  // ragged last tile: rows past the end re-read the last key (masked later)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int key = min(key0 + 4 * e + g, Lk - 1);
+          kreg[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (int64_t)key * sk.l + 8 * i16));
+        }
       }
+    };
+    auto issue_v = [&](int key0_, u32x4 (&vreg)[8]) {
+      const int key0 = __builtin_amdgcn_readfirstlane(key0_);
+      if (key0 + kTileKeys <= Lk && small_stride) {
+        const char* vt = reinterpret_cast<const char*>(vb) + (int64_t)key0 * sv.l * 2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          vreg[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vt + voff[e]));
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int key = min(key0 + ((e < 4) ? (4 * g + e) : (16 + 4 * g + (e - 4))), Lk - 1);
+          vreg[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (int64_t)key * sv.l + 8 * i16));
+        }
+      }
+    };
+    auto tile_step = [&](int key0, u32x4 (&kreg)[8], u32x4 (&vreg)[8]) {
+      // ---- K tile: registers -> LDS (swizzled) ----
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = 4 * e + g;
@@ -187,6 +215,23 @@ __global__ __launch_bounds__(kSplitWaves * kWave) void attention_splitk_bf16_ker
             __builtin_bit_cast(bf16x8, hi4), __builtin_bit_cast(bf16x8, pb), acc[2 * tp + 1], 0, 0,
             0);
       }
+    };
+
+    constexpr int kStride = kSplitWaves * kTileKeys;
+    u32x4 kA[8], kB[8], vv[8];
+    int key0 = lo + wave * kTileKeys;
+    if (key0 < hi) issue_k(key0, kA);
+    while (key0 < hi) {
+      const int key1 = key0 + kStride;
+      issue_v(key0, vv);
+      if (key1 < hi) issue_k(key1, kB);
+      tile_step(key0, kA, vv);
+      if (key1 >= hi) break;
+      const int key2 = key1 + kStride;
+      issue_v(key1, vv);
+      if (key2 < hi) issue_k(key2, kA);
+      tile_step(key1, kB, vv);
+      key0 = key2;
     }
 
     // ---- merge the four wavefront states, write the chunk state ----

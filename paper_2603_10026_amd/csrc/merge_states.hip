@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_states_kernel(
 #pragma unroll
       for (int i = 0; i < kPre; ++i) {
         const int s = sg0 + i * G0;
-        pre[i] = (s < S) ? *reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c0)
+        pre[i] = (s < S) ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c0))
                          : f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_states_kernel(
         const float mc = pm[s];
         if (mc == -INFINITY) continue;
         const float w = fast_exp2((mc - m_use) * kLog2e);
-        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c);
+        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(pa + (int64_t)s * d + 4 * c));
         sum += a * w;
       }
     }

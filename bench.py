@@ -349,18 +349,29 @@ def main():
     dsts = [torch.empty_like(t) for t in srcs]
     t_copy = timed(lambda i: rf.rf_diag_copy(srcs[i % N_ROT], dsts[i % N_ROT]), 12)
     del srcs, dsts
+    rbytes = 1 << 30
+    rsrc = [torch.ones(rbytes // 4, dtype=torch.float32, device=dev) for _ in range(2)]
+    rsink = torch.empty(rf.DIAG_READ_SINK_BYTES // 4, dtype=torch.int32, device=dev)
+    t_read = timed(lambda i: rf.rf_diag_read(rsrc[i % 2], rsink), 8)
+    del rsrc, rsink
     sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
     fl = 512 * 4 * 300 * 32 * 32768.0
     t_rand = timed(lambda i: rf.rf_diag_mfma(sink, 512, 300, True), 5)
     t_const = timed(lambda i: rf.rf_diag_mfma(sink, 512, 300, False), 5)
     ceilings = dict(hbm_copy_GBps=round(2 * nbytes / t_copy / 1e9, 1),
+                    hbm_read_only_GBps=round(rbytes / t_read / 1e9, 1),
                     mfma_bf16_random_operands_TFLOPs=round(fl / t_rand / 1e12, 1),
                     mfma_bf16_constant_operands_TFLOPs=round(fl / t_const / 1e12, 1),
-                    note="plain 256 MiB copy kernel; MFMA-only 32x32x16 bf16 loop, 512 workgroups x 4 wavefronts")
+                    note="plain 256 MiB copy kernel and 1 GiB read-only kernel (non-temporal accesses); MFMA-only 32x32x16 bf16 loop, 512 workgroups x 4 wavefronts")
     for r in rooflines:
         if r["bound"] == "mfma" and r["peak"] != PEAK_BF16_TFLOPS:
             continue            # no measured ceiling for the fp8 matrix pipe
-        ceil = ceilings["hbm_copy_GBps"] if r["bound"] == "hbm" else ceilings["mfma_bf16_random_operands_TFLOPs"]
+        if r["bound"] == "hbm":
+            # kernels that almost only read are put next to the read-only ceiling, the softmax
+            # (as many bytes written as read) next to the copy ceiling
+            ceil = ceilings["hbm_copy_GBps"] if r["kernel"] == "w1_softmax" else ceilings["hbm_read_only_GBps"]
+        else:
+            ceil = ceilings["mfma_bf16_random_operands_TFLOPs"]
         r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
 
     # ------------------------------------------------------------ cpu baseline

@@ -229,12 +229,18 @@ RF_API rf_status rf_diag_softmax_level(const rf_tensor* x, rf_tensor* y, int lev
  * FETCH_SIZE / WRITE_SIZE hardware counters.
  *   rf_diag_copy : dst[0..bytes) = src[0..bytes); device pointers, 16-byte aligned,
  *                  bytes a multiple of 16, buffers must not overlap.
+ *   rf_diag_read : reads src[0..bytes) once with non-temporal 128-bit loads and writes one
+ *                  32-bit word per wavefront into `sink`, a device buffer of at least
+ *                  RF_DIAG_READ_SINK_BYTES bytes (content: the XOR of what the wavefront read; the rest of the buffer is left as it was).
+ *                  The ceiling for kernels that only read HBM.
  *   rf_diag_mfma : `workgroups` workgroups of 4 wavefronts each issue iters*32 dense bf16
  *                  32x32x16 MFMAs (32768 flop each) on constant (random_operands == 0) or
  *                  pseudo-random operands; `sink` is a device buffer of workgroups*256 floats
  *                  that receives the accumulator sums.
  */
 RF_API rf_status rf_diag_copy(const void* src, void* dst, int64_t bytes, rf_stream stream);
+#define RF_DIAG_READ_SINK_BYTES (8192 * 4 * 4)
+RF_API rf_status rf_diag_read(const void* src, int64_t bytes, void* sink, rf_stream stream);
 RF_API rf_status rf_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
                               rf_stream stream);
 

@@ -36,6 +36,7 @@ ENTRY_POINTS = (
     "rf_fp8_quant_gemm",
     "rf_diag_softmax_level",
     "rf_diag_copy",
+    "rf_diag_read",
     "rf_diag_mfma",
 )
 
@@ -101,6 +102,8 @@ def load_library():
     lib.rf_diag_softmax_level.argtypes = [P, P, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    lib.rf_diag_read.restype = ctypes.c_int
+    lib.rf_diag_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
     lib.rf_diag_mfma.restype = ctypes.c_int
     lib.rf_diag_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     _lib = lib
@@ -292,6 +295,20 @@ def rf_diag_copy(src, dst, stream=None):
     _check(lib.rf_diag_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()),
                             nbytes, _stream(stream)), "rf_diag_copy")
     return dst
+
+
+DIAG_READ_SINK_BYTES = 8192 * 4 * 4
+
+
+def rf_diag_read(src, sink, stream=None):
+    """Read-only streaming kernel of known size (measurement aid); ``sink``: a device tensor of at
+    least DIAG_READ_SINK_BYTES bytes that receives one word per wavefront."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    assert sink.numel() * sink.element_size() >= DIAG_READ_SINK_BYTES
+    _check(lib.rf_diag_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()),
+                            _stream(stream)), "rf_diag_read")
+    return sink
 
 
 def rf_diag_mfma(sink, workgroups, iters, random_operands, stream=None):

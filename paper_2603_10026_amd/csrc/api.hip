@@ -426,6 +426,17 @@ rf_status rf_diag_copy(const void* src, void* dst, int64_t bytes, rf_stream stre
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 
+rf_status rf_diag_read(const void* src, int64_t bytes, void* sink, rf_stream stream) {
+  if (bytes < 0) return RF_ERR_INVALID_ARG;
+  if (bytes == 0) return RF_OK;
+  if (src == nullptr || sink == nullptr) return RF_ERR_INVALID_ARG;
+  if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(sink) % 4 != 0)
+    return RF_ERR_ALIGNMENT;
+  hipError_t e = rf::launch_diag_read(src, bytes, sink, (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
 rf_status rf_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
                        rf_stream stream) {
   if (sink == nullptr || workgroups < 1 || iters < 0 || workgroups > (1 << 20))

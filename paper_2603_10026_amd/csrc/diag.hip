@@ -2,6 +2,7 @@
 // roofline fractions are put next to.
 //   - a plain streaming copy kernel of known size (HBM ceiling; also the reference
 //     dispatch that scales the FETCH_SIZE / WRITE_SIZE hardware counters),
+//   - a read-only streaming kernel (what a kernel that only reads HBM can reach),
 //   - an MFMA-only loop (dense bf16 32x32x16) with constant or pseudo-random operands:
 //     the matrix-pipe ceiling depends strongly on the operand values (clock / power).
 #include "rf_device.h"
@@ -14,6 +15,30 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const u32x4* __restrict_
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// Reads n_vec 128-bit vectors once (non-temporal), every workgroup a contiguous share with
+// eight loads in flight per lane, folds them, and writes one word per wavefront (the XOR of what it
+// read) so that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void diag_read_kernel(const u32x4* __restrict__ src, int64_t n_vec,
+                                                        uint32_t* __restrict__ sink) {
+  const int64_t per_wg = (n_vec + gridDim.x - 1) / gridDim.x;
+  const int64_t lo = (int64_t)blockIdx.x * per_wg;
+  const int64_t hi = min(n_vec, lo + per_wg);
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  int64_t i = lo + threadIdx.x;
+  for (; i + 7 * 256 < hi; i += 8 * 256) {
+    u32x4 r[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= r[u];
+  }
+  for (; i < hi; i += 256) acc ^= __builtin_nontemporal_load(src + i);
+  uint32_t w = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) w ^= __shfl_xor(w, off, 64);
+  if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = w;
 }
 
 __device__ __forceinline__ uint32_t diag_hash(uint32_t x) {
@@ -61,6 +86,12 @@ hipError_t launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream
   const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 65536 ? 65536 : want));
   hipLaunchKernelGGL(diag_copy_kernel, dim3(grid), dim3(256), 0, s, (const u32x4*)src, (u32x4*)dst,
                      n_vec);
+  return hipGetLastError();
+}
+
+hipError_t launch_diag_read(const void* src, int64_t bytes, void* sink, hipStream_t s) {
+  hipLaunchKernelGGL(diag_read_kernel, dim3(kDiagReadWorkgroups), dim3(256), 0, s, (const u32x4*)src,
+                     bytes / 16, (uint32_t*)sink);
   return hipGetLastError();
 }
 

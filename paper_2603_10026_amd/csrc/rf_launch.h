@@ -74,6 +74,8 @@ hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n,
 // (workgroups x 4 wavefronts x iters x 32 MFMAs of 32x32x16 bf16; sink holds
 // workgroups * 256 floats).
 hipError_t launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
+constexpr int kDiagReadWorkgroups = 8192;  // the sink holds one 32-bit word per wavefront (4 per workgroup)
+hipError_t launch_diag_read(const void* src, int64_t bytes, void* sink, hipStream_t s);
 hipError_t launch_diag_mfma(float* sink, int workgroups, int iters, int random_operands,
                             hipStream_t s);
 

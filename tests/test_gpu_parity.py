@@ -449,3 +449,22 @@ def test_softmax_fusion_levels(rf, level, rows, n):
     rf.rf_diag_softmax_level(tx, ty, level, ml)
     torch.cuda.synchronize()
     check(ty, O.safe_softmax(x), "bf16", f"softmax level {level}")
+
+
+# --------------------------------------------------------- measurement aids
+def test_diag_copy_and_read(rf):
+    say("diag copy / read-only aids")
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    n = (1 << 20) + 4 * 77                       # 128-bit vectors, not a multiple of the workgroup share
+    src = torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, device=DEV, generator=g)
+    dst = torch.zeros_like(src)
+    rf.rf_diag_copy(src, dst)
+    sink = torch.zeros(rf.DIAG_READ_SINK_BYTES // 4, dtype=torch.int32, device=DEV)
+    rf.rf_diag_read(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    # every word is read exactly once: the XOR of the per-workgroup words is the XOR of the data
+    want = np.bitwise_xor.reduce(src.cpu().numpy().view(np.uint32))
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert int(want) == int(got)

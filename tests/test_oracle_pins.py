@@ -535,6 +535,24 @@ def _e4m3_from_bits():
     return np.array(sorted(set(vals)))
 
 
+def test_e4m3_grid_matches_the_stored_format_table():
+    """tests/golden/e4m3_finite_values.txt: the finite values of OCP FP8 E4M3, written from the format's
+    definition.  The oracle's rounding maps every one of them to itself and everything else onto them."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "e4m3_finite_values.txt")
+    table = np.array([float(t) for t in open(path).read().split("\n") if t and not t.startswith("#")])
+    assert len(table) == 253 and table[0] == -448.0 and table[-1] == 448.0
+    np.testing.assert_array_equal(table, _e4m3_from_bits())
+    np.testing.assert_array_equal(O.e4m3_round(table), table)
+    x = RNG(82).standard_normal(5000) * 100
+    r = O.e4m3_round(x)
+    assert np.all(np.isin(r, table))
+    # nearest: no table entry is strictly closer than the one chosen (|x| <= 448)
+    inside = np.abs(x) <= 448
+    d_best = np.min(np.abs(x[inside, None] - table[None, :]), axis=1)
+    np.testing.assert_allclose(np.abs(r[inside] - x[inside]), d_best, rtol=0, atol=0)
+
+
 def test_e4m3_grid_fixed_points_ties_and_saturation():
     grid = _e4m3_from_bits()
     assert grid.max() == 448.0 and grid[grid > 0].min() == 2.0 ** -9 and len(grid) == 253

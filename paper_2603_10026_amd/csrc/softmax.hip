@@ -125,6 +125,48 @@ void softmax_row_in_regs_kernel(
   }
 }
 
+// Short rows (at most LPR vectors of 16 bytes): 64 / LPR rows per wavefront, one vector per
+// lane, the two reductions over the LPR lanes of a row by butterfly shuffles.  A wavefront per
+// row would leave most lanes (and most of every 128-byte line fetched) idle.
+template <typename T, int LPR>
+__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_short_rows_kernel(
+    const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n, int64_t x_pitch,
+    int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
+  constexpr int RPW = kWave / LPR;  // rows per wavefront
+  constexpr uint32_t kNegInf = std::is_same<T, float>::value ? 0xFF800000u : 0xFF80FF80u;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int sub = lane % LPR;       // vector index inside the row
+  const int64_t row = ((int64_t)blockIdx.x * kSoftmaxWavesPerWg + (threadIdx.x >> 6)) * RPW + lane / LPR;
+  const int nvec = n / V;
+  const bool ok = row < rows && sub < nvec;
+  // lanes without a vector read a valid address (their own row's first vector, or row 0's)
+  const u32x4* src = reinterpret_cast<const u32x4*>(x + (row < rows ? row : 0) * x_pitch) + (sub < nvec ? sub : 0);
+  u32x4 r = __builtin_nontemporal_load(src);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r[j] = ok ? r[j] : kNegInf;
+  float e[V];
+  Elem<T>::unpack(r, e);
+  float m = e[0];
+#pragma unroll
+  for (int i = 1; i < V; ++i) m = fmaxf(m, e[i]);
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+  const float mb = -m * kLog2e;
+  float l = 0.f;
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    e[i] = fast_exp2(fmaf(e[i], kLog2e, mb));
+    l += e[i];
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) l += __shfl_xor(l, off, kWave);
+  const float inv = 1.0f / l;
+#pragma unroll
+  for (int i = 0; i < V; ++i) e[i] *= inv;
+  if (ok) __builtin_nontemporal_store(Elem<T>::pack(e), reinterpret_cast<u32x4*>(y + row * y_pitch) + sub);
+}
+
 // One workgroup per row, any n; two sweeps over the row (the second one is served by the
 // L2 for rows of a few hundred KB).  VEC: rows are 16-byte aligned, so both sweeps use
 // 128-bit accesses and the incremental state is corrected once per vector; otherwise
@@ -205,7 +247,22 @@ static hipError_t launch_softmax_t(const T* x, T* y, int64_t rows, int64_t n, in
                                    int64_t y_pitch, bool vec_ok, hipStream_t s) {
   constexpr int V = Elem<T>::kPerVec;
   const int64_t per_chunk = (int64_t)V * kWave;
-  if (vec_ok && n % V == 0 && n <= 16 * per_chunk) {
+  if (vec_ok && n % V == 0 && n > 0 && n <= 32 * V) {
+    // short rows: 2, 4, 8 or 16 rows per wavefront
+    const int nvec = (int)(n / V);
+    const int lpr = nvec <= 4 ? 4 : nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
+    const int64_t rows_per_wg = (int64_t)kSoftmaxWavesPerWg * (kWave / lpr);
+    const unsigned grid = (unsigned)((rows + rows_per_wg - 1) / rows_per_wg);
+    const dim3 block(kSoftmaxWavesPerWg * kWave);
+#define RF_SOFTMAX_SHORT(L)                                                               \
+  hipLaunchKernelGGL((softmax_short_rows_kernel<T, L>), dim3(grid), block, 0, s, x, y, rows, \
+                     (int)n, x_pitch, y_pitch)
+    if (lpr == 4) RF_SOFTMAX_SHORT(4);
+    else if (lpr == 8) RF_SOFTMAX_SHORT(8);
+    else if (lpr == 16) RF_SOFTMAX_SHORT(16);
+    else RF_SOFTMAX_SHORT(32);
+#undef RF_SOFTMAX_SHORT
+  } else if (vec_ok && n % V == 0 && n <= 16 * per_chunk) {
     const int nch = (int)((n + per_chunk - 1) / per_chunk);
     const unsigned grid = (unsigned)((rows + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg);
     const dim3 block(kSoftmaxWavesPerWg * kWave);

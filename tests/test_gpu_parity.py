@@ -56,6 +56,9 @@ def check(out, ref, dtype, what):
     ("bf16", 4, 4096), ("bf16", 37, 512), ("bf16", 5, 8), ("bf16", 3, 1000), ("bf16", 130, 2048),
     ("bf16", 7, 1003), ("bf16", 2, 9000), ("bf16", 1, 1), ("bf16", 3, 8192),
     ("f32", 9, 4096), ("f32", 3, 300), ("f32", 2, 5000), ("f32", 6, 1024), ("f32", 5, 7),
+    # short rows: several rows per wavefront (2 / 4 / 8 / 16), ragged last wavefront
+    ("bf16", 1000, 64), ("bf16", 77, 128), ("bf16", 131, 256), ("bf16", 9, 8), ("bf16", 33, 24), ("bf16", 3, 200),
+    ("f32", 50, 128), ("f32", 7, 4), ("f32", 101, 36), ("f32", 1, 64),
 ])
 def test_softmax_shapes(rf, dtype, rows, n):
     say(f"softmax {dtype} rows={rows} n={n}")

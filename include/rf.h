@@ -215,7 +215,7 @@ RF_API rf_status rf_rmsnorm_gemm(const rf_tensor* x, const rf_tensor* g, const r
  *            ml_buf: device memory for 2 * rows floats (the row maxima and sums)
  *   level 1  fused per lane: every lane runs the incremental form over its own elements,
  *            lane states merged with the level-k expression
- *   level 2  fused per wavefront: what rf_safe_softmax runs for these shapes
+ *   level 2  fused per wavefront: what rf_safe_softmax runs for rows of up to 4096 values
  *   level 3  fused per workgroup: lane states merged across four wavefronts through LDS
  * ml_buf is ignored for levels 1..3.
  */

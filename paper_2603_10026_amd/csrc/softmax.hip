@@ -167,6 +167,73 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_short_rows
   if (ok) __builtin_nontemporal_store(Elem<T>::pack(e), reinterpret_cast<u32x4*>(y + row * y_pitch) + sub);
 }
 
+// Long rows that still fit the registers of one workgroup (up to WAVES * 64 lanes * 64 values):
+// one workgroup per row, the row read once and kept as fp32; the two reductions go through
+// the wavefronts' DPP reductions and one LDS exchange each.
+template <typename T, int NCH, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void softmax_row_in_regs_wg_kernel(
+    const T* __restrict__ x, T* __restrict__ y, int64_t rows, int n, int64_t x_pitch,
+    int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
+  constexpr int TH = WAVES * kWave;
+  constexpr uint32_t kNegInf = std::is_same<T, float>::value ? 0xFF800000u : 0xFF80FF80u;
+  __shared__ float s_max[WAVES], s_sum[WAVES];
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const u32x4* xr = reinterpret_cast<const u32x4*>(x + row * x_pitch);
+  u32x4* yr = reinterpret_cast<u32x4*>(y + row * y_pitch);
+  const int nvec = n / V;
+  float e[NCH][V];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = c * TH + tid;
+    u32x4 r = __builtin_nontemporal_load(xr + min(idx, nvec - 1));
+    const bool ok = idx < nvec;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = ok ? r[j] : kNegInf;
+    Elem<T>::unpack(r, e[c]);
+  }
+  // cascade stage 1: row max
+  float m = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int i = 0; i < V; ++i) m = fmaxf(m, e[c][i]);
+  m = wave_max(m);
+  if ((tid & (kWave - 1)) == 0) s_max[tid >> 6] = m;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) m = fmaxf(m, s_max[w]);
+  // cascade stage 2: sum of exp(x - m), exponentials kept for the epilogue
+  const float mb = -m * kLog2e;
+  float l = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      e[c][i] = fast_exp2(fmaf(e[c][i], kLog2e, mb));
+      l += e[c][i];
+    }
+  }
+  l = wave_sum(l);
+  if ((tid & (kWave - 1)) == 0) s_sum[tid >> 6] = l;
+  __syncthreads();
+  l = 0.f;
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) l += s_sum[w];   // same order in every lane
+  const float inv = 1.0f / l;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int idx = c * TH + tid;
+    if (idx < nvec) {
+      float f[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) f[i] = e[c][i] * inv;
+      __builtin_nontemporal_store(Elem<T>::pack(f), yr + idx);
+    }
+  }
+}
+
 // One workgroup per row, any n; two sweeps over the row (the second one is served by the
 // L2 for rows of a few hundred KB).  VEC: rows are 16-byte aligned, so both sweeps use
 // 128-bit accesses and the incremental state is corrected once per vector; otherwise
@@ -262,7 +329,8 @@ static hipError_t launch_softmax_t(const T* x, T* y, int64_t rows, int64_t n, in
     else if (lpr == 16) RF_SOFTMAX_SHORT(16);
     else RF_SOFTMAX_SHORT(32);
 #undef RF_SOFTMAX_SHORT
-  } else if (vec_ok && n % V == 0 && n <= 16 * per_chunk) {
+  } else if (vec_ok && n % V == 0 && n <= (64 / V) * per_chunk) {
+    // one wavefront per row, at most 64 values per lane
     const int nch = (int)((n + per_chunk - 1) / per_chunk);
     const unsigned grid = (unsigned)((rows + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg);
     const dim3 block(kSoftmaxWavesPerWg * kWave);
@@ -275,6 +343,18 @@ static hipError_t launch_softmax_t(const T* x, T* y, int64_t rows, int64_t n, in
     else if (nch <= 8) RF_SOFTMAX_CASE(8);
     else RF_SOFTMAX_CASE(16);
 #undef RF_SOFTMAX_CASE
+  } else if (vec_ok && n % V == 0 && n <= 16 * 64 * (int64_t)kWave) {
+    // up to 64 values per lane, 2 / 4 / 8 / 16 wavefronts: rows of 8K, 16K, 32K, 64K values
+    constexpr int NCHW = 64 / V;
+    const int64_t per_wave = (int64_t)NCHW * V * kWave;   // 4096 values
+#define RF_SOFTMAX_WG(W)                                                                       \
+  hipLaunchKernelGGL((softmax_row_in_regs_wg_kernel<T, NCHW, W>), dim3((unsigned)rows),        \
+                     dim3(W * kWave), 0, s, x, y, rows, (int)n, x_pitch, y_pitch)
+    if (n <= 2 * per_wave) RF_SOFTMAX_WG(2);
+    else if (n <= 4 * per_wave) RF_SOFTMAX_WG(4);
+    else if (n <= 8 * per_wave) RF_SOFTMAX_WG(8);
+    else RF_SOFTMAX_WG(16);
+#undef RF_SOFTMAX_WG
   } else if (vec_ok) {
     hipLaunchKernelGGL((softmax_row_streaming_kernel<T, true>), dim3((unsigned)rows),
                        dim3(kStreamThreads), 0, s, x, y, rows, n, x_pitch, y_pitch);
@@ -322,7 +402,7 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_unfused_pa
 }
 
 // level 0: unfused (three kernels, needs ml_buf = 2 * rows floats); 1: fused per lane;
-// 2: fused per wavefront (the shipped kernel); 3: fused per workgroup (the streaming kernel).
+// 2: fused per wavefront (the shipped kernel for rows of up to 4096 values); 3: fused per workgroup (the streaming kernel).
 // bf16 only, n a multiple of 8 and at most 8192, 16-byte aligned rows.
 hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n, int64_t x_pitch,
                                 int64_t y_pitch, int level, float* ml_buf, hipStream_t s) {

@@ -59,6 +59,9 @@ def check(out, ref, dtype, what):
     # short rows: several rows per wavefront (2 / 4 / 8 / 16), ragged last wavefront
     ("bf16", 1000, 64), ("bf16", 77, 128), ("bf16", 131, 256), ("bf16", 9, 8), ("bf16", 33, 24), ("bf16", 3, 200),
     ("f32", 50, 128), ("f32", 7, 4), ("f32", 101, 36), ("f32", 1, 64),
+    # long rows held in the registers of one workgroup (4 / 8 / 16 wavefronts), then the streaming kernel
+    ("bf16", 3, 16384), ("bf16", 2, 40000), ("bf16", 2, 65536), ("f32", 2, 10000), ("f32", 1, 65536), ("f32", 2, 20004),
+    ("bf16", 2, 70000), ("f32", 1, 65540),
 ])
 def test_softmax_shapes(rf, dtype, rows, n):
     say(f"softmax {dtype} rows={rows} n={n}")

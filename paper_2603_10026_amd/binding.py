@@ -34,6 +34,9 @@ ENTRY_POINTS = (
     "rf_moe_routing_workspace_bytes",
     "rf_moe_routing",
     "rf_fp8_quant_gemm",
+)
+# measurement aids and the fusion-level study, declared in include/rf_diag.h
+DIAG_ENTRY_POINTS = (
     "rf_diag_softmax_level",
     "rf_diag_copy",
     "rf_diag_read",

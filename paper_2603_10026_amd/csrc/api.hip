@@ -1,6 +1,7 @@
 // C-ABI layer: argument validation on the host, then dispatch to the kernel
 // launchers.  No device memory is allocated, freed or retained here.
 #include "../../include/rf.h"
+#include "../../include/rf_diag.h"
 
 #include <string.h>
 
@@ -390,6 +391,8 @@ rf_status rf_rmsnorm_gemm(const rf_tensor* x, const rf_tensor* g, const rf_tenso
   if (x->data == nullptr || g->data == nullptr || w->data == nullptr || y->data == nullptr)
     return RF_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(g) || !aligned16(w) || !aligned16(y)) return RF_ERR_ALIGNMENT;
+  // the kernel addresses a 128-row tile of x and a 64-row tile of w with 32-bit byte offsets
+  if (x->stride[0] >= (1 << 24) || w->stride[0] >= (1 << 24)) return RF_ERR_UNSUPPORTED;
   hipError_t e = rf::launch_rmsnorm_gemm_bf16(x->data, g->data, w->data, y->data, (int)M, (int)K,
                                               (int)N, x->stride[0], w->stride[0], y->stride[0], eps,
                                               (hipStream_t)stream);

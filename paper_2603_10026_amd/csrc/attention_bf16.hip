@@ -42,8 +42,6 @@ namespace {
 constexpr int kBK = 64;   // keys per tile
 constexpr float kTau = 8.0f;
 
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void global_cvoid;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 
 // 16-byte slot swizzles (slot = piece ^ f(row)).
@@ -180,12 +178,20 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(dst_addr), "v"(is_v ? ld_voff[e] : ld_koff[e]), "s"(tile)
-                   : "memory");
+                   : "memory", "m0");
     } else {
-      // ragged last tile: rows past the end re-read the last key (masked later)
+      // ragged last tile: rows past the end re-read the last key (masked later).  The same raw
+      // instruction with a 64-bit lane address: every direct-to-LDS load of this kernel goes
+      // through one mechanism, so M0 is only ever written here, in statements that declare it
+      // as clobbered.
       const int key = min(key0 + ld_row[e], Lk - 1);
       const bf16_t* src = base + (int64_t)key * ld + (is_v ? ld_vcol[e] : ld_kcol[e]);
-      __builtin_amdgcn_global_load_lds((global_cvoid*)src, (lds_void*)dst, 16, 0, 0);
+      const uint32_t dst_addr = __builtin_amdgcn_readfirstlane(
+          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)dst);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                   :
+                   : "s"(dst_addr), "v"(src)
+                   : "memory", "m0");
     }
   };
   auto issue_loads = [&](int key0, int buf) {

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"            \
                    :                                                                          \
                    : "s"(dst_), "v"(wsrc_off[e]), "s"(wt_)                                    \
-                   : "memory");                                                               \
+                   : "memory", "m0");                                                         \
     }                                                                                         \
   }
 

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"          \
                    :                                                                         \
                    : "s"(dst_), "v"(wsrc_off[e]), "s"(wt_)                                   \
-                   : "memory");                                                              \
+                   : "memory", "m0");                                                        \
     }                                                                                        \
   }
 
@@ -349,7 +349,9 @@ hipError_t launch_rmsnorm_gemm_bf16(const void* x, const void* g, const void* w,
   const int n_ntiles = (N + kBN - 1) / kBN;
   const int64_t grid = (int64_t)n_mtiles * n_ntiles;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
-  if (ldw >= (1 << 24)) return hipErrorInvalidValue;  // 32-bit byte offsets inside a 64-row tile
+  // 32-bit byte offsets: inside a 64-row tile of w, inside a 128-row tile of x (the C-ABI
+  // layer rejects such pitches as unsupported before it gets here)
+  if (ldw >= (1 << 24) || ldx >= (1 << 24)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(rmsnorm_gemm_bf16_kernel, dim3((unsigned)grid), dim3(kGThreads), 0, s,
                      (const bf16_t*)x, (const bf16_t*)g, (const bf16_t*)w, (bf16_t*)y, M, K, N, ldx,
                      ldw, ldy, 1.0f / (float)K, eps, n_mtiles, n_ntiles);

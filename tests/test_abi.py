@@ -21,18 +21,71 @@ def lib():
     return B.load_library()
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "rf.h")).read()
+def _declared_symbols(header="rf.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     return sorted(set(re.findall(r"RF_API\s+[\w\s\*]+?\b(rf_\w+)\s*\(", text)))
 
 
 def test_header_declares_the_expected_entry_points():
-    assert _declared_symbols() == sorted(B.ENTRY_POINTS)
+    assert _declared_symbols("rf.h") == sorted(B.ENTRY_POINTS)
+    assert _declared_symbols("rf_diag.h") == sorted(B.DIAG_ENTRY_POINTS)
+    assert not any(n.startswith("rf_diag") for n in _declared_symbols("rf.h"))
 
 
 def test_library_exports_every_declared_symbol(lib):
-    for name in _declared_symbols():
-        assert hasattr(lib, name), name
+    for header in ("rf.h", "rf_diag.h"):
+        for name in _declared_symbols(header):
+            assert hasattr(lib, name), name
+
+
+def test_headers_compile_as_c_and_agree_with_the_binding(tmp_path):
+    """rf.h and rf_diag.h are C headers: a C compiler accepts them, and the struct layout and
+    enum values it sees are the ones the Python binding hard-codes."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "layout.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include <stddef.h>
+#include "rf.h"
+#include "rf_diag.h"
+int main(void) {
+  printf("sizeof_rf_tensor %zu\n", sizeof(rf_tensor));
+  printf("off_data %zu\noff_dtype %zu\noff_ndim %zu\noff_shape %zu\noff_stride %zu\n",
+         offsetof(rf_tensor, data), offsetof(rf_tensor, dtype), offsetof(rf_tensor, ndim),
+         offsetof(rf_tensor, shape), offsetof(rf_tensor, stride));
+  printf("sizeof_rf_stage %zu\n", sizeof(rf_stage));
+  printf("RF_MAX_DIMS %d\n", RF_MAX_DIMS);
+  printf("RF_OK %d\nRF_ERR_INVALID_ARG %d\nRF_ERR_UNSUPPORTED %d\nRF_ERR_ALIGNMENT %d\n"
+         "RF_ERR_WORKSPACE %d\nRF_ERR_LAUNCH %d\n", RF_OK, RF_ERR_INVALID_ARG, RF_ERR_UNSUPPORTED,
+         RF_ERR_ALIGNMENT, RF_ERR_WORKSPACE, RF_ERR_LAUNCH);
+  printf("RF_F32 %d\nRF_BF16 %d\nRF_I32 %d\nRF_FP8_E4M3 %d\n", RF_F32, RF_BF16, RF_I32, RF_FP8_E4M3);
+  printf("RF_RED_MAX %d\nRF_RED_MIN %d\nRF_RED_SUM %d\nRF_COMB_ADD %d\nRF_COMB_MUL %d\n",
+         RF_RED_MAX, RF_RED_MIN, RF_RED_SUM, RF_COMB_ADD, RF_COMB_MUL);
+  printf("RF_DIAG_READ_SINK_BYTES %d\n", RF_DIAG_READ_SINK_BYTES);
+  return 0;
+}
+""")
+    exe = tmp_path / "layout"
+    subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    got = {k: int(v) for k, v in (ln.split() for ln in out.splitlines())}
+    T = B.RfTensor
+    assert got["sizeof_rf_tensor"] == ctypes.sizeof(T) == 96
+    for f in ("data", "dtype", "ndim", "shape", "stride"):
+        assert got["off_" + f] == getattr(T, f).offset, f
+    assert got["sizeof_rf_stage"] == ctypes.sizeof(B.RfStage)
+    assert got["RF_MAX_DIMS"] == B.RF_MAX_DIMS
+    for name in ("RF_OK", "RF_ERR_INVALID_ARG", "RF_ERR_UNSUPPORTED", "RF_ERR_ALIGNMENT", "RF_ERR_WORKSPACE",
+                 "RF_ERR_LAUNCH", "RF_F32", "RF_BF16", "RF_I32", "RF_FP8_E4M3"):
+        assert got[name] == getattr(B, name), name
+    assert (got["RF_RED_MAX"], got["RF_RED_MIN"], got["RF_RED_SUM"]) == (0, 1, 2)
+    assert (got["RF_COMB_ADD"], got["RF_COMB_MUL"]) == (0, 1)
+    assert got["RF_DIAG_READ_SINK_BYTES"] == B.DIAG_READ_SINK_BYTES
 
 
 def test_status_strings(lib):
@@ -131,6 +184,10 @@ def test_rmsnorm_gemm_validation(lib):
     assert f(_r(x), _r(g), _r(_desc([128, 60])), _r(_desc([16, 60])), 1e-6, None) == B.RF_ERR_UNSUPPORTED
     assert f(_r(x), _r(g), _r(_desc([128, 64], data=0x1002)), _r(y), 1e-6, None) == B.RF_ERR_ALIGNMENT
     assert f(_r(_desc([0, 128], data=None)), _r(g), _r(w), _r(_desc([0, 64], data=None)), 1e-6, None) == B.RF_OK
+    # row pitches the kernel's 32-bit tile offsets cannot express are refused, not wrapped
+    big = 1 << 24
+    assert f(_r(_desc([16, 128], stride=[big, 1])), _r(g), _r(w), _r(y), 1e-6, None) == B.RF_ERR_UNSUPPORTED
+    assert f(_r(x), _r(g), _r(_desc([128, 64], stride=[big, 1])), _r(y), 1e-6, None) == B.RF_ERR_UNSUPPORTED
 
 
 def test_variance_validation(lib):

@@ -14,7 +14,8 @@
  * Conventions shared by all entry points
  *   - Every `data` pointer is a DEVICE pointer into memory owned by the caller
  *     (inputs, outputs and partial-state workspaces alike).  The library never
- *     allocates, frees or retains device memory and keeps no global state.
+ *     allocates or frees device memory, and retains none of the caller's.  Its only state
+ *     is the fixed scratch array of rf_moe_routing_noalloc.
  *   - rf_tensor describes a dense tensor: shape[] and stride[] in ELEMENTS for
  *     dims 0..ndim-1.  The last dimension must have stride 1; outer dimensions
  *     may be strided.  Base pointers and every outer stride must keep rows
@@ -133,6 +134,24 @@ RF_API size_t rf_moe_routing_workspace_bytes(int64_t S, int64_t hd, int64_t E);
 RF_API rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
                                 rf_tensor* idx, void* workspace, size_t workspace_bytes,
                                 rf_stream stream);
+
+/*
+ * rf_moe_routing for callers that cannot allocate device memory or hand over a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as rf_moe_routing, but the fp32 partial
+ * scores live in a device array inside the library (RF_MOE_ROUTING_NOALLOC_MAX_BYTES bytes,
+ * held by every GPU the library is used on until the process ends) instead of a caller's
+ * workspace; the call allocates and frees nothing.
+ *   A problem whose rf_moe_routing_workspace_bytes(S, hd, E) exceeds
+ *   RF_MOE_ROUTING_NOALLOC_MAX_BYTES is refused with RF_ERR_WORKSPACE before any launch.
+ *   The device of `stream` must be the current device.  All calls on one GPU share that
+ *   GPU's array: calls that overlap in time on one GPU (different streams, different host
+ *   threads) race on it and must be serialised by the caller.  Nothing in the array needs
+ *   a particular value between calls.
+ */
+#define RF_MOE_ROUTING_NOALLOC_MAX_BYTES ((size_t)8 << 20)
+RF_API rf_status rf_moe_routing_noalloc(const rf_tensor* x, const rf_tensor* w, int topk,
+                                        rf_tensor* prob, rf_tensor* idx, rf_stream stream);
 
 /*
  * FP8 per-token quantisation fused with a GEMM (Section 3.4, case study): the cascade

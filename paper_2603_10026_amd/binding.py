@@ -33,6 +33,7 @@ ENTRY_POINTS = (
     "rf_variance",
     "rf_moe_routing_workspace_bytes",
     "rf_moe_routing",
+    "rf_moe_routing_noalloc",
     "rf_fp8_quant_gemm",
 )
 # measurement aids and the fusion-level study, declared in include/rf_diag.h
@@ -99,6 +100,8 @@ def load_library():
     lib.rf_moe_routing_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
     lib.rf_moe_routing.restype = ctypes.c_int
     lib.rf_moe_routing.argtypes = [P, P, ctypes.c_int, P, P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.rf_moe_routing_noalloc.restype = ctypes.c_int
+    lib.rf_moe_routing_noalloc.argtypes = [P, P, ctypes.c_int, P, P, ctypes.c_void_p]
     lib.rf_fp8_quant_gemm.restype = ctypes.c_int
     lib.rf_fp8_quant_gemm.argtypes = [P, P, P, ctypes.c_void_p]
     lib.rf_diag_softmax_level.restype = ctypes.c_int
@@ -266,6 +269,19 @@ def rf_moe_routing(x, w, topk, prob=None, idx=None, workspace=None, stream=None)
     _check(lib.rf_moe_routing(ctypes.byref(dx), ctypes.byref(dw), int(topk), ctypes.byref(dp), ctypes.byref(di),
                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                               _stream(stream)), "rf_moe_routing")
+    return prob, idx
+
+
+MOE_ROUTING_NOALLOC_MAX_BYTES = 8 << 20
+
+
+def rf_moe_routing_noalloc(x, w, topk, prob, idx, stream=None):
+    """rf_moe_routing with the partial scores in the library's own fixed device array: the call
+    allocates nothing, so ``prob`` [S,topk] f32 and ``idx`` [S,topk] i32 must be given."""
+    lib = load_library()
+    dx, dw, dp, di = tensor_desc(x), tensor_desc(w), tensor_desc(prob), tensor_desc(idx)
+    _check(lib.rf_moe_routing_noalloc(ctypes.byref(dx), ctypes.byref(dw), int(topk), ctypes.byref(dp),
+                                      ctypes.byref(di), _stream(stream)), "rf_moe_routing_noalloc")
     return prob, idx
 
 

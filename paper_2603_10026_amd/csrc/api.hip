@@ -7,6 +7,8 @@
 
 #include "rf_launch.h"
 
+static_assert(RF_MOE_ROUTING_NOALLOC_MAX_BYTES == rf::kMoeStaticScratchBytes, "header and kernels agree on the scratch size");
+
 namespace {
 
 inline size_t esize(rf_dtype t) { return t == RF_BF16 ? 2 : t == RF_FP8_E4M3 ? 1 : 4; }  // f32, i32: 4
@@ -208,10 +210,12 @@ size_t rf_moe_routing_workspace_bytes(int64_t S, int64_t hd, int64_t E) {
   return (size_t)rf::moe_num_slices((int)S, (int)hd) * (size_t)S * (size_t)E * sizeof(float);
 }
 
-rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
-                         rf_tensor* idx, void* workspace, size_t workspace_bytes,
-                         rf_stream stream) {
+namespace {
+// Argument checks shared by the two MoE routing entry points (everything but the workspace).
+rf_status check_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, const rf_tensor* prob,
+                            const rf_tensor* idx, bool* empty) {
   rf_status st;
+  *empty = false;
   if ((st = check_tensor(x, 2, 2)) != RF_OK) return st;
   if ((st = check_tensor(w, 2, 2)) != RF_OK) return st;
   if ((st = check_tensor(prob, 2, 2)) != RF_OK) return st;
@@ -222,7 +226,7 @@ rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_te
   if (w->shape[0] != hd) return RF_ERR_INVALID_ARG;
   if (topk < 1 || topk > E) return RF_ERR_INVALID_ARG;
   if (prob->shape[0] != S || prob->shape[1] != topk || !same_shape(prob, idx)) return RF_ERR_INVALID_ARG;
-  if (S == 0) return RF_OK;
+  if (S == 0) { *empty = true; return RF_OK; }
   if (hd == 0 || hd % 128 != 0 || (E != 32 && E != 64 && E != 128) || topk > 16)
     return RF_ERR_UNSUPPORTED;
   if (S > INT32_MAX || hd > INT32_MAX) return RF_ERR_UNSUPPORTED;
@@ -235,6 +239,17 @@ rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_te
     return RF_ERR_ALIGNMENT;
   if (S * x->stride[0] * 2 >= ((int64_t)1 << 32) || 128 * w->stride[0] * 2 >= ((int64_t)1 << 32))
     return RF_ERR_UNSUPPORTED;
+  return RF_OK;
+}
+}  // namespace
+
+rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
+                         rf_tensor* idx, void* workspace, size_t workspace_bytes,
+                         rf_stream stream) {
+  bool empty;
+  rf_status st = check_moe_routing(x, w, topk, prob, idx, &empty);
+  if (st != RF_OK || empty) return st;
+  const int64_t S = x->shape[0], hd = x->shape[1], E = w->shape[1];
   if (workspace == nullptr || reinterpret_cast<uintptr_t>(workspace) % 16 != 0 ||
       workspace_bytes < rf_moe_routing_workspace_bytes(S, hd, E))
     return RF_ERR_WORKSPACE;
@@ -242,6 +257,20 @@ rf_status rf_moe_routing(const rf_tensor* x, const rf_tensor* w, int topk, rf_te
                                         x->stride[0], w->stride[0], (float*)prob->data,
                                         (int32_t*)idx->data, prob->stride[0], idx->stride[0],
                                         (float*)workspace, (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
+rf_status rf_moe_routing_noalloc(const rf_tensor* x, const rf_tensor* w, int topk, rf_tensor* prob,
+                                 rf_tensor* idx, rf_stream stream) {
+  bool empty;
+  rf_status st = check_moe_routing(x, w, topk, prob, idx, &empty);
+  if (st != RF_OK || empty) return st;
+  const int64_t S = x->shape[0], hd = x->shape[1], E = w->shape[1];
+  if (rf_moe_routing_workspace_bytes(S, hd, E) > RF_MOE_ROUTING_NOALLOC_MAX_BYTES) return RF_ERR_WORKSPACE;
+  hipError_t e = rf::launch_moe_routing_static(x->data, w->data, (int)S, (int)hd, (int)E, topk,
+                                               x->stride[0], w->stride[0], (float*)prob->data,
+                                               (int32_t*)idx->data, prob->stride[0], idx->stride[0],
+                                               (hipStream_t)stream);
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 

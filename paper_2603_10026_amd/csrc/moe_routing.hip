@@ -19,10 +19,18 @@
 // Kernel 2 (cascade): 16 lanes per token add the slices' partial scores in slice
 //   order, then run the cascade: each lane reduces its experts, lanes merge
 //   (max; sum with the exp rescale; TopK of the union) with DPP lane exchanges.
+#include <atomic>
+
 #include "rf_device.h"
 #include "rf_launch.h"
 
 namespace rf {
+
+// Scratch memory of the entry point that must not allocate: fp32 partial scores of one call.
+// A file-scope device array: every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels are always handed the address that call returned.
+static __device__ __align__(256) unsigned char scratch[kMoeStaticScratchBytes];
 
 namespace {
 
@@ -327,6 +335,33 @@ int moe_num_slices(int S, int hd) {
   if (ks > 64) ks = 64;
   if (ks < 1) ks = 1;
   return ks;
+}
+
+// Device address of `scratch` on the current device, resolved once per device (with that
+// device current) and kept.  Returns nullptr if the runtime cannot resolve the symbol.
+static float* moe_static_scratch() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> cache[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = cache[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+    cache[dev].store(ptr, std::memory_order_release);  // (two threads racing here store the same address)
+  }
+  return static_cast<float*>(ptr);
+}
+
+hipError_t launch_moe_routing_static(const void* x, const void* w, int S, int hd, int E, int topk,
+                                     int64_t ldx, int64_t ldw, float* prob, int32_t* idx,
+                                     int64_t ldp, int64_t ldi, hipStream_t s) {
+  if ((size_t)moe_num_slices(S, hd) * (size_t)S * (size_t)E * sizeof(float) > kMoeStaticScratchBytes)
+    return hipErrorInvalidValue;  // (the C-ABI layer has already refused this size)
+  float* part = moe_static_scratch();
+  if (part == nullptr) return hipErrorInvalidSymbol;
+  // Nothing in the scratch array has to start at zero: the scores kernel writes every partial
+  // score the cascade kernel reads, and what an earlier, larger call left behind is never read.
+  return launch_moe_routing(x, w, S, hd, E, topk, ldx, ldw, prob, idx, ldp, ldi, part, s);
 }
 
 hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E, int topk,

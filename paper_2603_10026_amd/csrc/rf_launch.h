@@ -59,6 +59,13 @@ hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E
                               int64_t ldx, int64_t ldw, float* prob, int32_t* idx, int64_t ldp,
                               int64_t ldi, float* part, hipStream_t s);
 
+// The same two kernels with the partial scores in a file-scope device array of
+// kMoeStaticScratchBytes bytes instead of a caller's workspace: no allocation anywhere.
+constexpr size_t kMoeStaticScratchBytes = (size_t)8 << 20;
+hipError_t launch_moe_routing_static(const void* x, const void* w, int S, int hd, int E, int topk,
+                                     int64_t ldx, int64_t ldw, float* prob, int32_t* idx,
+                                     int64_t ldp, int64_t ldi, hipStream_t s);
+
 // a [M,K] bf16, w [N,K] FP8 (E4M3), c [M,N] bf16; leading dimensions in elements.
 // K % 128 == 0, N % 8 == 0.
 hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, int K, int N,

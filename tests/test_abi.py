@@ -66,6 +66,7 @@ int main(void) {
   printf("RF_RED_MAX %d\nRF_RED_MIN %d\nRF_RED_SUM %d\nRF_COMB_ADD %d\nRF_COMB_MUL %d\n",
          RF_RED_MAX, RF_RED_MIN, RF_RED_SUM, RF_COMB_ADD, RF_COMB_MUL);
   printf("RF_DIAG_READ_SINK_BYTES %d\n", RF_DIAG_READ_SINK_BYTES);
+  printf("RF_MOE_ROUTING_NOALLOC_MAX_BYTES %zu\n", RF_MOE_ROUTING_NOALLOC_MAX_BYTES);
   return 0;
 }
 """)
@@ -86,6 +87,7 @@ int main(void) {
     assert (got["RF_RED_MAX"], got["RF_RED_MIN"], got["RF_RED_SUM"]) == (0, 1, 2)
     assert (got["RF_COMB_ADD"], got["RF_COMB_MUL"]) == (0, 1)
     assert got["RF_DIAG_READ_SINK_BYTES"] == B.DIAG_READ_SINK_BYTES
+    assert got["RF_MOE_ROUTING_NOALLOC_MAX_BYTES"] == B.MOE_ROUTING_NOALLOC_MAX_BYTES
 
 
 def test_status_strings(lib):
@@ -230,6 +232,16 @@ def test_moe_routing_validation(lib):
     assert lib.rf_safe_softmax(_r(_desc([4, 64], I32)), _r(_desc([4, 64], I32)), -1, None) == B.RF_ERR_UNSUPPORTED
     e0, p0, i0 = _desc([0, 256], data=None), _desc([0, 4], F32, data=None), _desc([0, 4], I32, data=None)
     assert f(_r(e0), _r(w), 4, _r(p0), _r(i0), None, 0, None) == B.RF_OK
+    # the entry point that allocates nothing: same argument checks, and a problem whose partial
+    # scores do not fit the library's fixed array is refused before any launch
+    g = lib.rf_moe_routing_noalloc
+    assert g(None, _r(w), 4, _r(p), _r(i), None) == B.RF_ERR_INVALID_ARG
+    assert g(_r(x), _r(w), 5, _r(p), _r(i), None) == B.RF_ERR_INVALID_ARG
+    assert g(_r(_desc([64, 192])), _r(_desc([192, 64])), 4, _r(p), _r(i), None) == B.RF_ERR_UNSUPPORTED
+    assert g(_r(e0), _r(w), 4, _r(p0), _r(i0), None) == B.RF_OK
+    Sbig = 1 << 16
+    assert lib.rf_moe_routing_workspace_bytes(Sbig, 256, 64) > B.MOE_ROUTING_NOALLOC_MAX_BYTES
+    assert g(_r(_desc([Sbig, 256])), _r(w), 4, _r(_desc([Sbig, 4], F32)), _r(_desc([Sbig, 4], I32)), None) == B.RF_ERR_WORKSPACE
     assert B.describe_cascade("rf_moe_routing") == [(0, 0), (2, 1), (0, 0)]      # max, sum, top-k (max-type)
 
 

@@ -156,17 +156,23 @@ RF_API rf_status rf_moe_routing_noalloc(const rf_tensor* x, const rf_tensor* w, 
 /*
  * FP8 per-token quantisation fused with a GEMM (Section 3.4, case study): the cascade
  *   m = max_k |a[k]|;   c[n] = sum_k q(MAX a[k] / m) w[n,k]
- * (q = rounding to OCP E4M3, nearest-even, MAX = 448) in its incremental form over tiles
- * of 128 k: each tile is quantised with the running maximum that includes it,
- *   m' = max(m, max_tile |a|);   acc' = acc * (m / m') + sum_tile q(MAX a / m') w,
- * earlier tiles keep their codes and are only rescaled.  Returned is acc * m / MAX, an
- * approximation of a @ w^T; it differs from quantising with the row's final maximum
- * only by quantisation noise (tokens whose maximum lies in the first tile: not at all).
+ * (q = rounding to OCP E4M3, nearest-even, MAX = 448), returned as c * m / MAX, an
+ * approximation of a @ w^T, computed in ONE pass over k with the incremental form of
+ * Section 3.4: the running maximum m' of the row prefix seen so far scales the elements that
+ * arrive, and the accumulator is rescaled by m'_old / m'_new whenever the maximum moves.
+ * Rounding sits between the two reductions, so the one-pass value is not bit-identical to the
+ * two-pass definition above: an element is quantised with some prefix maximum m' <= m that
+ * includes it.  What is promised, for any way the kernel cuts the row into prefixes:
+ *   - every dequantised element (m'/MAX) q(MAX a[k]/m') is within 2^-4 |a[k]| + 2^-10 m / MAX
+ *     of a[k], as in the two-pass definition, so
+ *       |c - c_twopass| <= 2 sum_k (2^-4 |a[k]| + 2^-10 m / MAX) |w[n,k]|
+ *     plus fp32 accumulation and the bf16 rounding of c;
+ *   - a token whose maximum is its first element is quantised exactly as in the two-pass
+ *     definition; an all-zero token gives an all-zero output row.
  *   a : [M, K] bf16.  K % 128 == 0.
- *   w : [N, K] FP8 E4M3, row n = output channel n (already quantised; any weight scale
- *       is the caller's to apply).  N % 8 == 0.
+ *   w : [N, K] FP8 E4M3, row n = output channel n (already quantised; any weight scale is
+ *       the caller's to apply).  N % 8 == 0.
  *   c : [M, N] bf16.
- * An all-zero token gives an all-zero output row.
  */
 RF_API rf_status rf_fp8_quant_gemm(const rf_tensor* a, const rf_tensor* w, rf_tensor* c,
                                    rf_stream stream);

@@ -1,14 +1,15 @@
 """GPU parity at the full benchmark sizes, in the launch configuration that
-bench.py times.  The inputs are generated on the device from the benchmark
-seeds; the oracle is evaluated on sampled outputs it can compute one by one
-(rows of softmax / attention / GEMM, whole (batch, head) pairs of decode), on
-host copies of exactly the device values.  Properties that hold at any size
-(softmax rows sum to one) are checked on the whole output.
+bench.py times, on the WHOLE output of every workload.  The inputs are generated
+on the device from the benchmark seeds; host copies of exactly the device values
+feed the oracle, which is evaluated for every output element (it takes seconds
+per workload on the host cores: its matmul steps go through the BLAS).  Output
+buffers are filled with NaN before the launch, so an output tile that no
+workgroup wrote cannot pass.
 
-Tolerance as in the small-size tests: max|err| <= tol * max|ref| with
-max|ref| over the sampled reference values (a subset of the full tensor, hence
-never looser than the full-tensor rule would be by more than sampling noise;
-the per-row relative check below is stricter than either).
+Tolerance as in the small-size tests: max|err| <= tol * max|ref| over the whole
+output tensor (the task's rule), and on top of it a bound for every row (or
+every (batch, head) block) against its own scale, which is what keeps causal
+attention honest: row 0 equals V[0] (|ref| ~ 4) while late rows are ~0.05.
 """
 import sys
 
@@ -18,6 +19,9 @@ import torch
 
 from oracle import rf_oracle as O
 from paper_2603_10026_amd import inputs as I
+
+sys.path.insert(0, __file__.rsplit("/", 1)[0])
+import fp8_checks as F  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -37,17 +41,26 @@ def say(msg):
 
 
 def check_rows(out_rows, ref_rows, tol, what, row_tol=None):
+    """out_rows, ref_rows: [rows, n].  Global rule over all rows given, then every row against
+    its own scale."""
     out_rows = np.asarray(out_rows, dtype=np.float64)
     ref_rows = np.asarray(ref_rows, dtype=np.float64)
-    assert np.all(np.isfinite(out_rows)), what
+    assert out_rows.shape == ref_rows.shape, (what, out_rows.shape, ref_rows.shape)
+    assert np.all(np.isfinite(out_rows)), f"{what}: non-finite (unwritten?) output"
     scale = float(np.max(np.abs(ref_rows)))
     err = float(np.max(np.abs(out_rows - ref_rows)))
-    print(f"        {what}: {len(ref_rows)} sampled rows, max|err|={err:.3e} max|ref|={scale:.3e} "
+    print(f"        {what}: {len(ref_rows)} rows, max|err|={err:.3e} max|ref|={scale:.3e} "
           f"ratio={err / scale:.2e}", flush=True)
     assert err <= tol * scale, what
-    if row_tol is not None:     # every sampled row against its own scale
-        for o, r in zip(out_rows, ref_rows):
-            assert np.max(np.abs(o - r)) <= row_tol * np.max(np.abs(r)), what
+    if row_tol is not None:
+        row_err = np.max(np.abs(out_rows - ref_rows), axis=1)
+        row_scale = np.max(np.abs(ref_rows), axis=1)
+        bad = np.nonzero(row_err > row_tol * row_scale)[0]
+        assert bad.size == 0, (what, "rows beyond their own bound", bad[:8], row_err[bad[:8]], row_scale[bad[:8]])
+
+
+def nan_like(shape, dtype):
+    return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
 
 
 def test_workload0_attention_f32_full(rf):
@@ -55,31 +68,31 @@ def test_workload0_attention_f32_full(rf):
     say(c["name"])
     q, k, v = I.attention_inputs_device(I.SEED_BASE + 0, c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "f32", DEV)
     sc = I.default_scale(c["d"])
-    o = rf.rf_cascade_attention(q, k, v, sc, False)
+    o = rf.rf_cascade_attention(q, k, v, sc, False, o=nan_like(q.shape, q.dtype))
     torch.cuda.synchronize()
     ref = O.attention(I.to_numpy(q), I.to_numpy(k), I.to_numpy(v), sc, False)
-    out = I.to_numpy(o)
-    err, scale = np.max(np.abs(out - ref)), np.max(np.abs(ref))
-    print(f"        full output: max|err|={err:.3e} max|ref|={scale:.3e}", flush=True)
-    assert err <= 1e-5 * scale
+    check_rows(I.to_numpy(o).reshape(-1, c["d"]), ref.reshape(-1, c["d"]), 1e-5, "attention f32, whole output", row_tol=1e-5)
 
 
 def test_workload1_softmax_full(rf):
     c = W[1]
     say(c["name"])
     x = I.softmax_inputs_device(I.SEED_BASE + 1, c["rows"], c["n"], c["sigma"], "bf16", DEV)
-    y = rf.rf_safe_softmax(x)
+    y = rf.rf_safe_softmax(x, nan_like(x.shape, x.dtype))
     torch.cuda.synchronize()
-    # property over the whole output: rows sum to 1 (bf16 output rounding: 4096 terms of 2^-9 relative error)
-    sums = y.to(torch.float32).sum(dim=1)
-    assert float((sums - 1.0).abs().max()) < 5e-3
-    assert bool((y >= 0).all())
-    rng = np.random.Generator(np.random.PCG64(11))
-    rows = np.unique(np.concatenate([[0, 1, c["rows"] - 1, c["rows"] - 2, 3, 4 * 8191 + 3],
-                                     rng.integers(0, c["rows"], size=58)]))
-    xs = I.to_numpy(x[torch.from_numpy(rows).to(DEV)])
-    ys = I.to_numpy(y[torch.from_numpy(rows).to(DEV)])
-    check_rows(ys, O.safe_softmax(xs), 2e-2, "softmax rows", row_tol=2e-2)
+    # every row, in blocks of 2048 rows so that the fp64 copies stay small
+    step = 2048
+    for r0 in range(0, c["rows"], step):
+        xs = I.to_numpy(x[r0:r0 + step])
+        ys = I.to_numpy(y[r0:r0 + step])
+        out = np.asarray(ys, dtype=np.float64)
+        ref = O.safe_softmax(xs)
+        assert np.all(np.isfinite(out)), f"softmax rows {r0}..: non-finite output"
+        assert np.max(np.abs(out - ref)) <= 2e-2 * np.max(np.abs(ref))
+        assert np.all(np.max(np.abs(out - ref), axis=1) <= 2e-2 * np.max(np.abs(ref), axis=1))
+        # rows sum to 1 (bf16 output rounding: 4096 terms of 2^-9 relative error)
+        assert np.max(np.abs(out.sum(axis=1) - 1.0)) < 5e-3
+    print(f"        softmax: all {c['rows']} rows within 2e-2 of their own maximum", flush=True)
 
 
 @pytest.mark.parametrize("causal", [False, True])
@@ -88,25 +101,27 @@ def test_workload2_prefill_full(rf, causal):
     say(f"{c['name']} causal={causal}")
     q, k, v = I.attention_inputs_device(I.SEED_BASE + 2, c["B"], c["Hq"], c["Hkv"], c["Lq"], c["Lk"], c["d"], "bf16", DEV)
     sc = I.default_scale(c["d"])
-    o = rf.rf_cascade_attention(q, k, v, sc, causal)
+    o = rf.rf_cascade_attention(q, k, v, sc, causal, o=nan_like(q.shape, q.dtype))
     torch.cuda.synchronize()
-    assert bool(torch.isfinite(o.to(torch.float32)).all())
-    rng = np.random.Generator(np.random.PCG64(12))
-    # two whole heads (first and last) + scattered rows incl. tile boundaries and the first/last query
-    L = c["Lq"]
-    picks = [(0, 0, i) for i in (0, 1, 31, 32, 63, 64, 127, 128, 129, 1023, 1024, L - 2, L - 1)]
-    picks += [(c["B"] - 1, c["Hq"] - 1, i) for i in (0, 5, 127, 128, 2047)]
-    picks += [(int(rng.integers(c["B"])), int(rng.integers(c["Hq"])), int(rng.integers(L))) for _ in range(46)]
-    heads = sorted({(b, h) for b, h, _ in picks})
-    host = {bh: tuple(I.to_numpy(t[bh[0], bh[1]])[None, None] for t in (q, k, v)) for bh in heads}
-    outs, refs = [], []
-    for (b, h, i) in picks:
-        qh, kh, vh = host[(b, h)]
-        refs.append(O.attention_rows(qh, kh, vh, sc, causal, [(0, 0, i)])[0])
-        outs.append(I.to_numpy(o[b, h, i]))
-    # under the causal mask row 0 equals V[0] (|ref| ~ 4) while late rows are ~0.05: the per-row
-    # check (5e-2 of the row's own max) keeps those rows honest
-    check_rows(outs, refs, 2e-2, "prefill rows", row_tol=5e-2)
+    assert bool(torch.isfinite(o.to(torch.float32)).all()), "an output tile was not written"
+    # every (batch, head), every query row, every element; one head at a time on the host
+    gmax_ref, gmax_err, worst_row = 0.0, 0.0, 0.0
+    for b in range(c["B"]):
+        for h in range(c["Hq"]):
+            qh, kh, vh = (I.to_numpy(t[b, h])[None, None] for t in (q, k, v))
+            ref = O.attention(qh, kh, vh, sc, causal)[0, 0]
+            out = np.asarray(I.to_numpy(o[b, h]), dtype=np.float64)
+            err = np.max(np.abs(out - ref), axis=1)
+            scale = np.max(np.abs(ref), axis=1)
+            # every row against its own scale (under the mask, row 0 is V[0] and late rows are tiny)
+            bad = np.nonzero(err > 5e-2 * scale)[0]
+            assert bad.size == 0, ("prefill", b, h, bad[:8], err[bad[:8]], scale[bad[:8]])
+            gmax_ref = max(gmax_ref, float(scale.max()))
+            gmax_err = max(gmax_err, float(err.max()))
+            worst_row = max(worst_row, float(np.max(err / scale)))
+    print(f"        prefill causal={causal}: {c['B'] * c['Hq']} heads x {c['Lq']} rows, max|err|={gmax_err:.3e} "
+          f"max|ref|={gmax_ref:.3e}, worst row err/scale {worst_row:.2e}", flush=True)
+    assert gmax_err <= 2e-2 * gmax_ref
 
 
 def test_workload3_decode_full(rf):
@@ -116,42 +131,44 @@ def test_workload3_decode_full(rf):
     sc = I.default_scale(c["d"])
     S = c["num_splits"]
     pm, pl, pacc = rf.alloc_partial_states(q, S)
+    for t in (pm, pl, pacc):
+        t.fill_(float("nan"))
     rf.rf_cascade_attention_splitk(q, k, v, S, pm, pl, pacc, sc, False)
-    o = rf.rf_merge_states(pm, pl, pacc, torch.empty_like(q))
+    o = rf.rf_merge_states(pm, pl, pacc, nan_like(q.shape, q.dtype))
     torch.cuda.synchronize()
     assert bool(torch.isfinite(o.to(torch.float32)).all())
     grp = c["Hq"] // c["Hkv"]
     outs, refs = [], []
-    for (b, hk) in [(0, 0), (c["B"] - 1, c["Hkv"] - 1), (7, 3)]:
-        kh, vh = (I.to_numpy(t[b, hk])[None, None] for t in (k, v))
-        qh = I.to_numpy(q[b, hk * grp:(hk + 1) * grp])[None]          # the 4 query heads of this KV head
-        ref = O.attention(qh, kh, vh, sc, False)[0]                   # [grp, 1, d]
-        refs.extend(ref[:, 0, :])
-        outs.extend(I.to_numpy(o[b, hk * grp:(hk + 1) * grp, 0]))
-        # the partial states of this group against the oracle's, chunk by chunk
-        rm, rl, racc = O.attention_partial_states(qh, kh, vh, sc, False, S)
-        gm = I.to_numpy(pm[b, hk * grp:(hk + 1) * grp])[None]
-        gl = I.to_numpy(pl[b, hk * grp:(hk + 1) * grp])[None]
-        ga = I.to_numpy(pacc[b, hk * grp:(hk + 1) * grp])[None]
-        shift = np.exp(gm - rm)
-        assert np.max(np.abs(gm - rm)) < 1e-3
-        assert np.max(np.abs(gl * shift - rl)) <= 2e-2 * np.max(np.abs(rl))
-        assert np.max(np.abs(ga * shift[..., None] - racc)) <= 2e-2 * np.max(np.abs(racc))
-    check_rows(outs, refs, 2e-2, "decode rows (3 KV heads x 4 query heads)", row_tol=2e-2)
+    # every (batch, KV head): the 4 query heads that share it, all 64 partial states and the merged rows
+    for b in range(c["B"]):
+        for hk in range(c["Hkv"]):
+            kh, vh = (I.to_numpy(t[b, hk])[None, None] for t in (k, v))
+            qh = I.to_numpy(q[b, hk * grp:(hk + 1) * grp])[None]          # [1, grp, 1, d]
+            ref = O.attention(qh, kh, vh, sc, False)[0]                   # the merge must be invisible
+            refs.extend(ref[:, 0, :])
+            outs.extend(I.to_numpy(o[b, hk * grp:(hk + 1) * grp, 0]))
+            rm, rl, racc = O.attention_partial_states(qh, kh, vh, sc, False, S)
+            gm = np.asarray(I.to_numpy(pm[b, hk * grp:(hk + 1) * grp])[None], dtype=np.float64)
+            gl = np.asarray(I.to_numpy(pl[b, hk * grp:(hk + 1) * grp])[None], dtype=np.float64)
+            ga = np.asarray(I.to_numpy(pacc[b, hk * grp:(hk + 1) * grp])[None], dtype=np.float64)
+            assert np.all(np.isfinite(gm)) and np.all(np.isfinite(gl)) and np.all(np.isfinite(ga)), (b, hk)
+            # the kernel's maximum is taken on bf16-product scores in fp32; compare the states at the oracle's reference point
+            assert np.max(np.abs(gm - rm)) < 1e-3, (b, hk)
+            shift = np.exp(gm - rm)
+            assert np.max(np.abs(gl * shift - rl)) <= 2e-2 * np.max(np.abs(rl)), (b, hk)
+            assert np.max(np.abs(ga * shift[..., None] - racc)) <= 2e-2 * np.max(np.abs(racc)), (b, hk)
+    check_rows(outs, refs, 2e-2, "decode, all rows (16 x 32 query heads) + all partial states", row_tol=2e-2)
 
 
 def test_workload4_rmsnorm_gemm_full(rf):
     c = W[4]
     say(c["name"])
     x, g, w = I.rmsnorm_gemm_inputs_device(I.SEED_BASE + 4, c["M"], c["K"], c["N"], c["w_sigma"], "bf16", DEV)
-    y = rf.rf_rmsnorm_gemm(x, g, w, eps=c["eps"])
+    y = rf.rf_rmsnorm_gemm(x, g, w, eps=c["eps"], y=nan_like((c["M"], c["N"]), x.dtype))
     torch.cuda.synchronize()
-    assert bool(torch.isfinite(y.to(torch.float32)).all())
-    rng = np.random.Generator(np.random.PCG64(14))
-    rows = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 257, c["M"] - 1], rng.integers(0, c["M"], size=24)]))
-    idx = torch.from_numpy(rows).to(DEV)
-    ref = O.rmsnorm_gemm(I.to_numpy(x[idx]), I.to_numpy(g), I.to_numpy(w), c["eps"])
-    check_rows(I.to_numpy(y[idx]), ref, 2e-2, "rmsnorm_gemm rows", row_tol=2e-2)
+    assert bool(torch.isfinite(y.to(torch.float32)).all()), "an output tile was not written"
+    ref = O.rmsnorm_gemm(I.to_numpy(x), I.to_numpy(g), I.to_numpy(w), c["eps"])      # every row
+    check_rows(I.to_numpy(y), ref, 2e-2, "rmsnorm_gemm, whole output", row_tol=2e-2)
 
 
 @pytest.mark.parametrize("key", sorted(I.VARIANCE_TABLE, key=lambda k: int(k[1:])))
@@ -197,12 +214,17 @@ def test_fp8_quant_gemm_full(rf, key):
     c = I.table_workload(key)
     say(f"{key} {c['name']}")
     a, w = I.fp8_quant_gemm_inputs_device(I.SEED_BASE + 7, c["M"], c["K"], c["N"], DEV)
-    out = rf.rf_fp8_quant_gemm(a, w)
+    # every 16th token gets its maximum in the first element: quantised with the final maximum from
+    # the first element on, those rows must reproduce the two-pass definition itself
+    first = torch.arange(5, c["M"], 16, device=DEV)
+    a[first, 0] = (a[first].float().abs().amax(dim=1) * 1.5).to(torch.bfloat16)
+    out = rf.rf_fp8_quant_gemm(a, w, c=nan_like((c["M"], c["N"]), torch.bfloat16))
     torch.cuda.synchronize()
-    # sampled token rows (tokens are independent): every 61st row plus the tile edges
-    rows = sorted(set(list(range(0, c["M"], 61)) + [127, 128, c["M"] - 1]))
-    ah = I.to_numpy(a[rows]).astype(np.float32)
+    assert bool(torch.isfinite(out.float()).all()), "an output tile was not written"
     wh = I.to_numpy(w.to(torch.float32))
-    ref = O.fp8_quant_gemm(ah, wh, 128)
-    check_rows(I.to_numpy(out[rows]), ref, 2e-2, "fp8_quant_gemm", row_tol=2e-2)
-    assert bool(torch.isfinite(out.float()).all())
+    first = first.cpu().numpy()
+    step = 1024                                  # every token, in blocks (fp64 copies of a stay small)
+    for r0 in range(0, c["M"], step):
+        rows = [int(r - r0) for r in first if r0 <= r < r0 + step]
+        F.check(I.to_numpy(out[r0:r0 + step]), I.to_numpy(a[r0:r0 + step]).astype(np.float32), wh,
+                f"fp8_quant_gemm {key} tokens {r0}..", first_max_rows=rows)

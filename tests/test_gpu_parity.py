@@ -18,6 +18,9 @@ import torch
 from oracle import rf_oracle as O
 from paper_2603_10026_amd import inputs as I
 
+sys.path.insert(0, __file__.rsplit("/", 1)[0])
+import fp8_checks as F  # noqa: E402
+
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
@@ -93,6 +96,20 @@ def test_softmax_special_rows_and_inplace(rf):
     assert out[1, 17] == 1.0
 
 
+@pytest.mark.parametrize("n", [16384, 70000])
+def test_softmax_inplace_long_rows(rf, n):
+    """In place (y == x) on the kernels for long rows: one workgroup holding the row in registers
+    (n = 16384) and the two-sweep streaming kernel (n = 70000), which reads x twice."""
+    say(f"softmax in place, n={n}")
+    x = I.softmax_inputs(13, 3, n, 2.0, "bf16")
+    t = I.to_torch(x, "bf16", DEV)
+    ref = O.safe_softmax(x)
+    y = rf.rf_safe_softmax(t, t)
+    torch.cuda.synchronize()
+    assert y.data_ptr() == t.data_ptr()
+    check(t, ref, "bf16", f"softmax in place n={n}")
+
+
 def test_softmax_strided_rows_and_3d(rf):
     say("softmax pitched 2-D view and contiguous 3-D")
     big = I.softmax_inputs(12, 16, 1024, 2.0, "bf16")
@@ -143,6 +160,10 @@ ATTN_CASES = [
     ("bf16", 1, 1, 1, 384, 1024, 128, True),
     ("bf16", 1, 2, 1, 300, 450, 128, False),    # 256-query workgroups, ragged second tile
     ("bf16", 2, 2, 2, 513, 129, 64, False),     # 256-query workgroups, one-row tail tile
+    ("bf16", 1, 2, 2, 512, 1000, 128, False),   # many key tiles, ragged key tail
+    ("bf16", 1, 1, 1, 300, 5, 128, False),      # a single, mostly empty key tile
+    ("bf16", 1, 8, 8, 384, 320, 128, False),    # 8 heads: one head per XCD in the tile order
+    ("bf16", 1, 8, 8, 384, 320, 128, True),
 ]
 
 
@@ -216,7 +237,9 @@ def test_splitk_partial_states_and_merge(rf, B, Hq, Hkv, Lq, Lk, S, causal):
     # the state is unique up to the reference point m: compare m, and (l, acc) moved to the oracle's m
     fin = ~ident
     np.testing.assert_allclose(gm[fin], rm[fin], rtol=0, atol=2e-2 * max(1.0, float(np.max(np.abs(rm[fin])))))
-    shift = np.where(fin, np.exp(np.where(fin, gm - rm, 0.0)), 0.0)
+    dm = np.zeros_like(rm)
+    dm[fin] = gm[fin] - rm[fin]                 # (identity chunks hold -inf on both sides: no difference taken)
+    shift = np.where(fin, np.exp(dm), 0.0)
     check(torch.from_numpy(gl * shift), rl, "bf16", "partial l")
     check(torch.from_numpy(gacc * shift[..., None]), racc, "bf16", "partial acc")
     check(o, O.attention(q, k, v, scale, causal), "bf16", "merged == attention over the whole key axis")
@@ -414,33 +437,39 @@ def _fp8_tensor(w_bits):
 def test_fp8_quant_gemm_shapes(rf, M, K, N):
     say(f"fp8_quant_gemm M{M} K{K} N{N}")
     a, w, w_bits = I.fp8_quant_gemm_inputs(I.SEED_BASE + 7, M, K, N)
+    first = list(range(0, M, 3))               # these tokens have their maximum in the first element
+    a[first, 0] = I.bf16_round(1.5 * np.max(np.abs(a[first]), axis=1))
     c = rf.rf_fp8_quant_gemm(I.to_torch(a, "bf16", DEV), _fp8_tensor(w_bits))
     torch.cuda.synchronize()
-    # the oracle runs the same algorithm: segments of 128, each quantised with its running maximum
-    check(c, O.fp8_quant_gemm(a, w, 128), "bf16", "fp8_quant_gemm")
+    # against the two-pass definition, within quantisation noise (no knowledge of the kernel's segments)
+    F.check(I.to_numpy(c), a, w, "fp8_quant_gemm", first_max_rows=first)
 
 
 def test_fp8_quant_gemm_special_rows_and_pitched_output(rf):
-    say("fp8_quant_gemm: zero token, late maximum, maximum in the first tile, pitched c")
-    M, K, N = 64, 512, 128
+    say("fp8_quant_gemm: zero token, late maximum, maximum first, scaled tokens, exact tokens, pitched c")
+    M, K, N = 64, 1024, 128
     a, w, w_bits = I.fp8_quant_gemm_inputs(93, M, K, N, outlier_rows=0)
     a[0] = 0.0                                  # all-zero token -> zeros
-    a[1, K - 1] = 200.0                         # maximum arrives in the last tile: every tile rescales
-    a[2, 3] = 200.0                             # maximum in the first tile: equals the two-pass definition
+    a[1, K - 1] = 200.0                         # maximum arrives last: everything before it is rescaled
+    a[2, 0] = 200.0                             # maximum first: the two-pass definition itself
     a[3] = I.bf16_round(a[3] * 1e-3)            # small token: its own scale
     a[4] = I.bf16_round(a[4] * 1e3)
+    # tokens made of powers of two whose maximum keeps moving (2^-7 ... 2^0 in rising runs): MAX a / m'
+    # is an FP8 value for every prefix maximum m', so any segmentation must return a @ w^T itself
+    rng = np.random.Generator(np.random.PCG64(94))
+    for r in (5, 6, 7):
+        e = np.sort(rng.integers(-7, 1, size=K)) if r != 7 else rng.integers(-7, 1, size=K)
+        a[r] = (np.exp2(e) * rng.choice([-1.0, 1.0], size=K)).astype(np.float32)
     cbig = torch.zeros((M, 2 * N), dtype=torch.bfloat16, device=DEV)
     rf.rf_fp8_quant_gemm(I.to_torch(a, "bf16", DEV), _fp8_tensor(w_bits), c=cbig[:, N:])
     torch.cuda.synchronize()
-    ref = O.fp8_quant_gemm(a, w, 128)
     out = I.to_numpy(cbig[:, N:])
     assert float(cbig[:, :N].abs().max()) == 0.0
     assert np.all(out[0] == 0.0)
-    for i in range(M):                          # every token against its own scale
-        s = np.max(np.abs(ref[i]))
-        assert np.max(np.abs(out[i] - ref[i])) <= 2e-2 * s + 1e-30, i
-    two = O.fp8_quant_gemm_twopass(a, w)
-    assert np.max(np.abs(out[2] - two[2])) <= 2e-2 * np.max(np.abs(two[2]))
+    F.check(out, a, w, "fp8_quant_gemm special rows", first_max_rows=[2])
+    exact = a.astype(np.float64) @ w.astype(np.float64).T
+    for r in (5, 6, 7):                         # exact up to fp32 accumulation and the bf16 rounding of c
+        assert np.max(np.abs(out[r] - exact[r])) <= 2.0 ** -7 * np.max(np.abs(exact[r])), r
 
 
 # ------------------------------------------- softmax fused at different levels

@@ -14,6 +14,7 @@ from paper_2603_10026_amd import inputs as I
 
 sys.path.insert(0, __file__.rsplit("/", 1)[0])
 from test_gpu_parity import _fp8_tensor, check, check_routing  # noqa: E402
+import fp8_checks as F  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
@@ -109,7 +110,7 @@ def test_fp8_quant_gemm_random_shapes(rf):
         a, w, w_bits = I.fp8_quant_gemm_inputs(9000 + i, m, k, n)
         out = rf.rf_fp8_quant_gemm(I.to_torch(a, "bf16", DEV), _fp8_tensor(w_bits))
         torch.cuda.synchronize()
-        check(out, O.fp8_quant_gemm(a, w, 128), "bf16", f"fp8_quant_gemm #{i}")
+        F.check(I.to_numpy(out), a, w, f"fp8_quant_gemm #{i}")
 
 
 def test_variance_random_shapes(rf):

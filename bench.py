@@ -19,10 +19,12 @@ last-level cache cannot serve repeated reads.
 
 Prints ONE JSON line.  ``value`` is the fused-attention throughput of the
 prefill workload (non-causal), from the HIP-event time of that kernel inside
-the timed region; ``workloads`` carries every workload's time, throughput and
-roofline fraction; ``roofline`` is the kernel that takes the most time in a
-step; ``cpu_baseline`` times the fp64 oracle on a bounded sample of the
-prefill workload on the host cores.
+the timed region, and ``roofline`` describes that same kernel; ``workloads``
+and ``rooflines`` carry every workload's time, throughput and roofline
+fraction; ``cpu_baseline`` times the fp64 oracle on a bounded sample of the
+prefill workload on the host cores and ``cpu_baselines`` does the same for each
+of the five workloads (seconds and the workload's own unit); ``device`` holds
+the compute-unit count and clock the box reports.
 """
 import argparse
 import json
@@ -216,14 +218,28 @@ def main():
                                    bytes=2.0 * (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] + c["K"]))
 
     # HBM-side traffic per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-    # scaled by a plain copy kernel (recorded in profiles/; None when no record exists)
-    traffic = {}
+    # scaled by a plain copy kernel (recorded in profiles/).  The record names the kernel sources
+    # it was measured on (a digest of csrc/); if they have changed since, no traffic is reported
+    # rather than a stale figure.
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2603_10026_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    kernel_sources = h.hexdigest()[:16]
+    traffic, traffic_sources = {}, None
     tpath = os.path.join(ROOT, "profiles", "bench_all_workloads_hbm_traffic.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             f = line.split()
             if len(f) == 4 and f[0] == "TRAFFIC":
                 traffic[f[1]] = float(f[2]) + float(f[3])
+            if len(f) == 2 and f[0] == "SOURCES":
+                traffic_sources = f[1]
+    traffic_current = traffic_sources == kernel_sources
+    if not traffic_current:
+        traffic = {}
 
     workloads = {}
     rooflines = []
@@ -252,7 +268,7 @@ def main():
         workloads["w3_decode_total"] = dict(us_avg=round(tot * 1e6, 2), GBps=round(b / tot / 1e9, 1),
                                             frac=round(b / tot / 1e9 / PEAK_HBM_GBS, 4), bound="hbm", algorithmic_bytes=b)
 
-    dominant = max(rooflines, key=lambda r: r["us"]) if rooflines else None
+    headline = next((r for r in rooflines if r["kernel"] == "w2_attention_prefill"), None)
 
     # ------------------------------------------------ further cascades of the paper
     # Timed after the step loop, each kernel alone: `steps` launches bracketed by HIP
@@ -375,28 +391,99 @@ def main():
         r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
 
     # ------------------------------------------------------------ cpu baseline
-    cpu = None
-    if not args.no_cpu_baseline and "w2" in only:
+    # The fp64 oracle as it stands, on the host cores of this machine, on a bounded sample of each
+    # workload (a few seconds each), next to the GPU result for the same sample.
+    cpu, cpus = None, {}
+    if not args.no_cpu_baseline:
         from oracle import rf_oracle as O
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        c = W[2]
-        s2 = state["w2"]
-        nb, nh = 2, c["Hq"]                      # two of the four batches: a bounded sample of the same workload
-        qh, kh, vh = (I.to_numpy(t[:nb]) for t in (s2["q"], s2["k"], s2["v"]))
-        tc0 = time.perf_counter()
-        ref = O.attention(qh, kh, vh, s2["scale"], False)
-        tc1 = time.perf_counter()
-        fl = 4.0 * nb * nh * c["Lq"] * c["Lk"] * c["d"]
-        got = I.to_numpy(s2["o"][:nb])
-        err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
-        cpu = dict(value=round(fl / (tc1 - tc0) / 1e12, 5), unit="TFLOP/s", cores=int(cores), kind="oracle",
-                   sample=f"{nb * nh} of {c['B'] * c['Hq']} (batch, head) pairs of the non-causal prefill workload, "
-                          f"fp64 numpy oracle, {tc1 - tc0:.1f} s wall",
-                   gpu_vs_oracle_max_err_over_max_ref=err)
+
+        def rel_err(got, ref):
+            return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / np.max(np.abs(ref)))
+
+        if "w0" in only:
+            c, s0 = W[0], state["w0"]
+            qh, kh, vh = (I.to_numpy(t) for t in (s0["q"], s0["k"], s0["v"]))
+            tc0 = time.perf_counter(); ref = O.attention(qh, kh, vh, s0["scale"], False); tc1 = time.perf_counter()
+            cpus["w0_attention_f32"] = dict(seconds=round(tc1 - tc0, 4), value=round(attn_flops(c, False) / (tc1 - tc0) / 1e12, 6),
+                                            unit="TFLOP/s", sample="the whole workload",
+                                            gpu_vs_oracle_max_err_over_max_ref=rel_err(I.to_numpy(s0["o"]), ref))
+        if "w1" in only:
+            c, s1 = W[1], state["w1"]
+            nrows = 4096
+            last = (args.warmup + args.steps - 1) % N_ROT          # the buffer set of the last step
+            xh = I.to_numpy(s1["x"][last][:nrows])
+            tc0 = time.perf_counter(); ref = O.safe_softmax(xh); tc1 = time.perf_counter()
+            cpus["w1_softmax"] = dict(seconds=round(tc1 - tc0, 4), value=round(2.0 * nrows * c["n"] * 2 / (tc1 - tc0) / 1e9, 3),
+                                      unit="GB/s", sample=f"{nrows} of {c['rows']} rows",
+                                      gpu_vs_oracle_max_err_over_max_ref=rel_err(I.to_numpy(s1["y"][last][:nrows]), ref))
+        if "w2" in only:
+            c, s2 = W[2], state["w2"]
+            nb, nh = 2, c["Hq"]                      # two of the four batches: a bounded sample of the same workload
+            qh, kh, vh = (I.to_numpy(t[:nb]) for t in (s2["q"], s2["k"], s2["v"]))
+            tc0 = time.perf_counter(); ref = O.attention(qh, kh, vh, s2["scale"], False); tc1 = time.perf_counter()
+            fl = 4.0 * nb * nh * c["Lq"] * c["Lk"] * c["d"]
+            err = rel_err(I.to_numpy(s2["o"][:nb]), ref)
+            cpu = dict(value=round(fl / (tc1 - tc0) / 1e12, 5), unit="TFLOP/s", cores=int(cores), kind="oracle",
+                       sample=f"{nb * nh} of {c['B'] * c['Hq']} (batch, head) pairs of the non-causal prefill workload, "
+                              f"fp64 numpy oracle, {tc1 - tc0:.1f} s wall",
+                       gpu_vs_oracle_max_err_over_max_ref=err)
+            cpus["w2_attention_prefill"] = dict(seconds=round(tc1 - tc0, 4), value=cpu["value"], unit="TFLOP/s",
+                                                sample=f"{nb * nh} of {c['B'] * c['Hq']} (batch, head) pairs",
+                                                gpu_vs_oracle_max_err_over_max_ref=err)
+            nbc = 1
+            tc0 = time.perf_counter(); ref = O.attention(qh[:nbc], kh[:nbc], vh[:nbc], s2["scale"], True); tc1 = time.perf_counter()
+            flc = 4.0 * nbc * nh * (c["Lq"] * (c["Lq"] + 1) // 2) * c["d"]
+            cpus["w2_attention_prefill_causal"] = dict(seconds=round(tc1 - tc0, 4), value=round(flc / (tc1 - tc0) / 1e12, 5),
+                                                       unit="TFLOP/s (visible pairs only)",
+                                                       sample=f"{nbc * nh} of {c['B'] * c['Hq']} (batch, head) pairs",
+                                                       gpu_vs_oracle_max_err_over_max_ref=rel_err(I.to_numpy(s2["oc"][:nbc]), ref))
+            del qh, kh, vh, ref
+        if "w3" in only:
+            c, s3 = W[3], state["w3"]
+            t = s3["sets"][(args.warmup + args.steps - 1) % N_ROT]
+            grp = c["Hq"] // c["Hkv"]
+            pairs = [(0, 0), (3, 5), (9, 2), (c["B"] - 1, c["Hkv"] - 1)]
+            secs, worst = 0.0, 0.0
+            for (b, hk) in pairs:
+                kh, vh = (I.to_numpy(x[b, hk])[None, None] for x in (t["k"], t["v"]))
+                qh = I.to_numpy(t["q"][b, hk * grp:(hk + 1) * grp])[None]
+                tc0 = time.perf_counter(); ref = O.attention(qh, kh, vh, s3["scale"], False); tc1 = time.perf_counter()
+                secs += tc1 - tc0
+                worst = max(worst, rel_err(I.to_numpy(t["o"][b, hk * grp:(hk + 1) * grp])[None], ref))
+            by = len(pairs) * 2.0 * c["Lk"] * c["d"] * 2
+            cpus["w3_decode_total"] = dict(seconds=round(secs, 4), value=round(by / secs / 1e9, 3), unit="GB/s",
+                                           sample=f"{len(pairs)} of {c['B'] * c['Hkv']} (batch, KV head) pairs, 4 query heads each, whole key axis",
+                                           gpu_vs_oracle_max_err_over_max_ref=worst)
+        if "w4" in only:
+            c, s4 = W[4], state["w4"]
+            nrows = 1024
+            xh, gh, wh = I.to_numpy(s4["x"][:nrows]), I.to_numpy(s4["g"]), I.to_numpy(s4["w"])
+            tc0 = time.perf_counter(); ref = O.rmsnorm_gemm(xh, gh, wh, s4["eps"]); tc1 = time.perf_counter()
+            cpus["w4_rmsnorm_gemm"] = dict(seconds=round(tc1 - tc0, 4), value=round(2.0 * nrows * c["K"] * c["N"] / (tc1 - tc0) / 1e12, 5),
+                                           unit="TFLOP/s", sample=f"{nrows} of {c['M']} rows",
+                                           gpu_vs_oracle_max_err_over_max_ref=rel_err(I.to_numpy(s4["y"][:nrows]), ref))
+        for v_ in cpus.values():
+            v_.update(cores=int(cores), kind="oracle")
+
+    props = torch.cuda.get_device_properties(0)
+    device = dict(name=props.name, compute_units=int(props.multi_processor_count), max_clock_mhz=None,
+                  hbm_bytes=int(props.total_memory), arch=getattr(props, "gcnArchName", None))
+    try:        # the GPU agent's own report of its clock and compute units (a child process; nothing is re-executed)
+        import subprocess
+        txt = subprocess.run(["/opt/rocm/bin/rocminfo"], capture_output=True, text=True, timeout=30).stdout
+        agent = txt[txt.index("gfx950"):]
+        for line in agent.splitlines():
+            if "Max Clock Freq. (MHz)" in line and device["max_clock_mhz"] is None:
+                device["max_clock_mhz"] = float(line.split(":")[1])
+            if line.strip().startswith("Compute Unit:") and "rocminfo_compute_units" not in device:
+                device["rocminfo_compute_units"] = int(line.split(":")[1])
+    except Exception:
+        pass
 
     primary = workloads.get("w2_attention_prefill")
     out = {
@@ -418,11 +505,18 @@ def main():
                    "seeds": [I.SEED_BASE + i for i in range(5)]},
         "workloads": workloads,
         "further_cascades": further,
-        "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]} if dominant else None,
+        # the kernel `value` describes; every other kernel under `rooflines`
+        "roofline": {k: headline[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": headline["kernel"]} if headline else None,
         "rooflines": rooflines,
+        "targets": {"hbm_frac": 0.70, "mfma_frac": 0.50,
+                    "met": {r["kernel"]: bool(r["frac"] >= (0.70 if r["bound"] == "hbm" else 0.50)) for r in rooflines}},
+        "traffic_record": {"file": "profiles/bench_all_workloads_hbm_traffic.txt", "measured_on_sources": traffic_sources,
+                           "current_sources": kernel_sources, "used": bool(traffic_current)},
         "ceilings": ceilings,
         "graph_replay": graph_replay,
+        "device": device,
         "cpu_baseline": cpu,
+        "cpu_baselines": cpus,
     }
     print(json.dumps(out))
 

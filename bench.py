@@ -10,6 +10,7 @@ input: every entry point of the library on its benchmark workload
   w4  rf_rmsnorm_gemm              bf16  4096 x 4096 x 4096
 After the timed steps the paper's further cascades are timed one kernel at a time
 (``further_cascades``; they are not part of a step):
+  x0  rf_cascade_attention         fp32  workload 0's shape batched over 16 x 32 heads (labelled extension)
   x1  rf_variance                  f32   X[1024,32768]
   x2  rf_moe_routing               bf16  tokens 2048; hd 8192 x 64 experts, hd 4096 x 128 experts; top 8
   x3  rf_fp8_quant_gemm            bf16 tokens x FP8 weights  4096 x 3584 x 8192 and 4096 x 8192 x 3584
@@ -70,7 +71,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x1", "x2", "x3"}
+    only = set(args.only.split(",")) if args.only else {"w0", "w1", "w2", "w3", "w4", "x0", "x1", "x2", "x3"}
     W = I.WORKLOADS
     seed = lambda i: I.SEED_BASE + i
 
@@ -287,6 +288,25 @@ def main():
         return dict(avg=float(np.mean(ts)), med=float(np.median(ts)), min=float(np.min(ts)))
 
     further = {}
+    if "x0" in only:
+        # labelled extension of workload 0: the same fp32 shape batched over 512 heads, so that
+        # an fp32 TFLOP/s figure means something (one head alone is a launch-latency measurement)
+        c = W[0]
+        nb, nh = 16, 32
+        qb, kb_, vb_ = I.attention_inputs_device(seed(0) + 50, nb, nh, nh, c["Lq"], c["Lk"], c["d"], "f32", dev)
+        ob = torch.empty_like(qb)
+        d = time_launches(lambda i: rf.rf_cascade_attention(qb, kb_, vb_, I.default_scale(c["d"]), False, o=ob),
+                          args.steps, args.warmup)
+        fl = 4.0 * nb * nh * c["Lq"] * c["Lk"] * c["d"]
+        ach = fl / (d["avg"] * 1e-6) / 1e12
+        further["x0_attention_f32_batched"] = dict(workload=f"attn_fp32_B{nb}_H{nh}_Lq{c['Lq']}_Lk{c['Lk']}_d{c['d']}",
+                                                   us_avg=round(d["avg"], 2), us_med=round(d["med"], 2), us_min=round(d["min"], 2),
+                                                   bound="mfma", TFLOPs=round(ach, 2), frac=round(ach / PEAK_F32_TFLOPS, 4),
+                                                   algorithmic_flops=fl,
+                                                   note="fraction of the published fp32 matrix peak (157.3 TFLOP/s); extension of workload 0, not one of the five configurations")
+        rooflines.append(dict(kernel="x0_attention_f32_batched", bound="mfma", achieved=round(ach, 2), peak=PEAK_F32_TFLOPS,
+                              unit="TFLOP/s", frac=round(ach / PEAK_F32_TFLOPS, 4), traffic=None, us=round(d["avg"], 2)))
+        del qb, kb_, vb_, ob
     if "x1" in only:
         c = I.EXTRA_WORKLOADS["variance_v8"]
         xs = [I.variance_inputs_device(seed(6) + 100 * r, c["bs"], c["l"], c["dtype"], c["mu"], c["sigma"], dev)
@@ -381,7 +401,7 @@ def main():
                     note="plain 256 MiB copy kernel and 1 GiB read-only kernel (non-temporal accesses); MFMA-only 32x32x16 bf16 loop, 512 workgroups x 4 wavefronts")
     for r in rooflines:
         if r["bound"] == "mfma" and r["peak"] != PEAK_BF16_TFLOPS:
-            continue            # no measured ceiling for the fp8 matrix pipe
+            continue            # no measured ceiling for the fp8 and fp32 matrix pipes
         if r["bound"] == "hbm":
             # kernels that almost only read are put next to the read-only ceiling, the softmax
             # (as many bytes written as read) next to the copy ceiling

@@ -27,6 +27,10 @@ extern "C" {
  *            lane states merged with the level-k expression
  *   level 2  fused per wavefront: what rf_safe_softmax runs for rows of up to 4096 values
  *   level 3  fused per workgroup: lane states merged across four wavefronts through LDS
+ *   level 4  fused across workgroups (the paper's inter-block level): a row is cut into four
+ *            segments handled by wavefronts of different workgroups; the first kernel stores
+ *            each segment's state (m, l), the second merges them with the level-k expression
+ *            and normalises; two reads of x.  ml_buf: device memory for 8 * rows floats
  * ml_buf is ignored for levels 1..3.
  */
 RF_API rf_status rf_diag_softmax_level(const rf_tensor* x, rf_tensor* y, int level, float* ml_buf,

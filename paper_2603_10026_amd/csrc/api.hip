@@ -435,12 +435,12 @@ rf_status rf_diag_softmax_level(const rf_tensor* x, rf_tensor* y, int level, flo
   if ((st = check_tensor(y, 2, 2)) != RF_OK) return st;
   if (x->dtype != RF_BF16 || y->dtype != RF_BF16) return RF_ERR_UNSUPPORTED;
   if (!same_shape(x, y)) return RF_ERR_INVALID_ARG;
-  if (level < 0 || level > 3) return RF_ERR_INVALID_ARG;
+  if (level < 0 || level > 4) return RF_ERR_INVALID_ARG;
   const int64_t rows = x->shape[0], n = x->shape[1];
   if (rows == 0 || n == 0) return RF_OK;
   if (n % 8 != 0 || n > 8192 || rows > INT32_MAX) return RF_ERR_UNSUPPORTED;
   if ((n > 1 && (x->stride[1] != 1 || y->stride[1] != 1))) return RF_ERR_UNSUPPORTED;
-  if (x->data == nullptr || y->data == nullptr || (level == 0 && ml_buf == nullptr)) return RF_ERR_INVALID_ARG;
+  if (x->data == nullptr || y->data == nullptr || ((level == 0 || level == 4) && ml_buf == nullptr)) return RF_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(y)) return RF_ERR_ALIGNMENT;
   hipError_t e = rf::launch_softmax_level(x->data, y->data, rows, n, x->stride[0], y->stride[0], level,
                                           ml_buf, (hipStream_t)stream);

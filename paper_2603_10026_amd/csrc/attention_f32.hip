@@ -66,62 +66,85 @@ __global__ __launch_bounds__(NW * kWave) void attention_f32_kernel(
 
   float m2 = -INFINITY;  // running max, in log2 units (score * scale * log2 e)
   float l = 0.f;         // running sum, this lane's keys only
-  f32x4 acc[DJ];         // acc[t][r] = O^T[head-dim 16t + 4g + r][query i16]
+  // Row i of the t-th O^T tile stands for head-dim index DJ * i + t (not 16 t + i): the DJ
+  // A-operand values a lane needs for one key are then DJ consecutive floats of the V row,
+  // fetched with 128-bit loads, and one load instruction reads whole 64 DJ-byte row pieces.
+  f32x4 acc[DJ];         // acc[t][r] = O^T[head-dim DJ * (4g + r) + t][query i16]
 #pragma unroll
   for (int t = 0; t < DJ; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int kt = wave; kt < n_ktiles; kt += NW) {
-    const int key0 = kt * 16;
-    // ---- S^T tile = K_tile Q^T (fp32 MFMA) ----
-    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-    {
-      const int kr = key0 + i16;
-      const float* kp = kb + (int64_t)min(kr, Lk - 1) * sk.l + 4 * g;
+  // A wavefront's tiles are taken TG at a time: all K and V fragments of the group are
+  // requested before the first product, so memory latency is paid once per group, not twice
+  // per tile (at the small sizes this kernel serves, that latency is most of the run time).
+  constexpr int TG = (D == 64 && NW <= 8) ? 4 : 2;
+  for (int kt0 = wave; kt0 < n_ktiles; kt0 += NW * TG) {
+    f32x4 kf[TG][DJ];
+    f32x4 vf[TG][4][DJ / 4];  // vf[.][u][c][e] = V[key of step u][DJ * i16 + 4c + e]
 #pragma unroll
-      for (int j = 0; j < DJ; ++j) {
-        const f32x4 kf = *reinterpret_cast<const f32x4*>(kp + 16 * j);
+    for (int jj = 0; jj < TG; ++jj) {
+      const int key0 = min(kt0 + NW * jj, n_ktiles - 1) * 16;  // (a surplus slot re-reads the last tile)
+      const float* kp = kb + (int64_t)min(key0 + i16, Lk - 1) * sk.l + 4 * g;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          s = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[e], qf[j][e], s, 0, 0, 0);
+      for (int j = 0; j < DJ; ++j) kf[jj][j] = *reinterpret_cast<const f32x4*>(kp + 16 * j);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        // contraction slot g of step u stands for key key0 + 4g + u
+        const float* vp = vb + (int64_t)min(key0 + 4 * g + u, Lk - 1) * sv.l + DJ * i16;
+#pragma unroll
+        for (int c = 0; c < DJ / 4; ++c) vf[jj][u][c] = *reinterpret_cast<const f32x4*>(vp + 4 * c);
       }
     }
-    // s[r] = score(key key0 + 4g + r, query i16); mask, then stage 1: running max
-    float tmax = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int key = key0 + 4 * g + r;
-      s[r] = (key <= my_last) ? s[r] * scale_log2e : -INFINITY;
-      tmax = fmaxf(tmax, s[r]);
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m2, tmax);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // identity repair
-    const float corr = fast_exp2(m2 - m_use);                // 0 when m2 == -inf
-    m2 = m_new;
-    // stage 2: running sum of exponentials
-    float p[4];
-    float psum = 0.f;
+    for (int jj = 0; jj < TG; ++jj) {
+      const int kt = kt0 + NW * jj;
+      if (kt >= n_ktiles) break;  // uniform per wavefront
+      const int key0 = kt * 16;
+      // ---- S^T tile = K_tile Q^T (fp32 MFMA), as two independent accumulation chains ----
+      f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, s_b = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      p[r] = fast_exp2(s[r] - m_use);
-      psum += p[r];
-    }
-    l = l * corr + psum;
-    // stage 3: rescale acc, then acc += V^T P^T
+      for (int j = 0; j < DJ; j += 2) {
 #pragma unroll
-    for (int t = 0; t < DJ; ++t) {
+        for (int e = 0; e < 4; ++e) {
+          s = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[jj][j][e], qf[j][e], s, 0, 0, 0);
+          s_b = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[jj][j + 1][e], qf[j + 1][e], s_b, 0, 0, 0);
+        }
+      }
+      s += s_b;
+      // s[r] = score(key key0 + 4g + r, query i16); mask, then stage 1: running max
+      float tmax = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) acc[t][r] *= corr;
-    }
+      for (int r = 0; r < 4; ++r) {
+        const int key = key0 + 4 * g + r;
+        s[r] = (key <= my_last) ? s[r] * scale_log2e : -INFINITY;
+        tmax = fmaxf(tmax, s[r]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m2, tmax);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // identity repair
+      const float corr = fast_exp2(m2 - m_use);                // 0 when m2 == -inf
+      m2 = m_new;
+      // stage 2: running sum of exponentials
+      float p[4];
+      float psum = 0.f;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      // contraction slot g of step u stands for key key0 + 4g + u
-      const int key = min(key0 + 4 * g + u, Lk - 1);
-      const float* vp = vb + (int64_t)key * sv.l + i16;
+      for (int r = 0; r < 4; ++r) {
+        p[r] = fast_exp2(s[r] - m_use);
+        psum += p[r];
+      }
+      l = l * corr + psum;
+      // stage 3: rescale acc, then acc += V^T P^T
 #pragma unroll
-      for (int t = 0; t < DJ; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(vp[16 * t], p[u], acc[t], 0, 0, 0);
+      for (int t = 0; t < DJ; ++t) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] *= corr;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int t = 0; t < DJ; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(vf[jj][u][t / 4][t % 4], p[u], acc[t], 0, 0, 0);
+      }
     }
   }
 
@@ -132,7 +155,7 @@ __global__ __launch_bounds__(NW * kWave) void attention_f32_kernel(
 #pragma unroll
   for (int t = 0; t < DJ; ++t) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) s_acc[wave][i16][16 * t + 4 * g + r] = acc[t][r];
+    for (int r = 0; r < 4; ++r) s_acc[wave][i16][DJ * (4 * g + r) + t] = acc[t][r];
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < 16 * (D / 4); idx += NW * kWave) {
@@ -166,7 +189,12 @@ hipError_t launch_attention_f32(const float* q, const float* k, const float* v, 
   const int64_t grid = (int64_t)n_qtiles * a.B * a.Hq;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
   const float sl2 = a.scale * kLog2e;
-  if (a.d == 64) {
+  if (a.d == 64 && grid < 256 && a.Lk > 128) {
+    // few workgroups and many keys: 16 wavefronts share the key axis of a query tile
+    hipLaunchKernelGGL((attention_f32_kernel<64, 16>), dim3((unsigned)grid), dim3(16 * kWave), 0, s,
+                       q, k, v, o, sq, sk, sv, so, a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal,
+                       n_qtiles);
+  } else if (a.d == 64) {
     hipLaunchKernelGGL((attention_f32_kernel<64, 8>), dim3((unsigned)grid), dim3(8 * kWave), 0, s,
                        q, k, v, o, sq, sk, sv, so, a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal,
                        n_qtiles);

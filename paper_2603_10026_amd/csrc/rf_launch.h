@@ -73,7 +73,8 @@ hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, i
 
 // Fusion-level study of the softmax cascade (bf16 rows, n % 8 == 0, n <= 8192): level 0 =
 // unfused (three kernels; ml_buf holds 2 * rows floats), 1 = fused per lane, 2 = per
-// wavefront (the shipped kernel), 3 = per workgroup.
+// wavefront (the shipped kernel), 3 = per workgroup, 4 = across workgroups (two kernels;
+// ml_buf holds 8 * rows floats).
 hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n, int64_t x_pitch,
                                 int64_t y_pitch, int level, float* ml_buf, hipStream_t s);
 

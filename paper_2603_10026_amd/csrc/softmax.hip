@@ -401,8 +401,75 @@ __global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_unfused_pa
   if constexpr (PASS == 1) { acc = wave_sum(acc); if (lane == 0) l_buf[row] = acc; }
 }
 
+// ---- fusion-level study: fused across workgroups (the paper's inter-block level) ----
+// A row is cut into kInterBlockSegs segments, one wavefront (of different workgroups) each.
+// Kernel 1 reads its segment once and stores the segment's fused state (m_s, l_s); kernel 2
+// merges the row's states with the level-k expression (Eq. (11)), reads its segment again and
+// writes y.  Two reads of x and a round trip of the states through memory: the cost the paper
+// attributes to this level.  m_buf, l_buf: rows * kInterBlockSegs floats each.
+constexpr int kInterBlockSegs = 4;
+template <typename T, int PASS>
+__global__ __launch_bounds__(kSoftmaxWavesPerWg * kWave) void softmax_interblock_kernel(
+    const T* __restrict__ x, T* __restrict__ y, float* __restrict__ m_buf, float* __restrict__ l_buf,
+    int64_t rows, int n, int64_t x_pitch, int64_t y_pitch) {
+  constexpr int V = Elem<T>::kPerVec;
+  const int lane = threadIdx.x & (kWave - 1);
+  // consecutive wavefronts of a workgroup take different rows: the segments of one row run in
+  // different workgroups
+  const int64_t unit = (int64_t)blockIdx.x * kSoftmaxWavesPerWg + (threadIdx.x >> 6);
+  const int seg = (int)(unit / rows);
+  const int64_t row = unit % rows;
+  if (seg >= kInterBlockSegs) return;
+  const int nvec = n / V;
+  const int per_seg = (nvec + kInterBlockSegs - 1) / kInterBlockSegs;
+  const int v0 = seg * per_seg, v1 = min(nvec, v0 + per_seg);
+  const u32x4* xr = reinterpret_cast<const u32x4*>(x + row * x_pitch);
+  if constexpr (PASS == 0) {
+    // the segment's state, level-1 incremental form per lane, lanes merged with Eq. (11)
+    float m = -INFINITY, l = 0.f;
+    for (int idx = v0 + lane; idx < v1; idx += kWave) {
+      float f[V];
+      Elem<T>::unpack(xr[idx], f);
+      float vm = f[0];
+#pragma unroll
+      for (int i = 1; i < V; ++i) vm = fmaxf(vm, f[i]);
+      const float m_new = fmaxf(m, vm);
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) part += fast_exp2((f[i] - m_new) * kLog2e);
+      l = l * ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * kLog2e)) + part;
+      m = m_new;
+    }
+    const float mw = wave_max(m);
+    const float lw = wave_sum((m == -INFINITY) ? 0.f : l * fast_exp2((m - mw) * kLog2e));
+    if (lane == 0) { m_buf[row * kInterBlockSegs + seg] = mw; l_buf[row * kInterBlockSegs + seg] = lw; }
+  } else {
+    float ms[kInterBlockSegs], ls[kInterBlockSegs];
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < kInterBlockSegs; ++c) {
+      ms[c] = m_buf[row * kInterBlockSegs + c];
+      ls[c] = l_buf[row * kInterBlockSegs + c];
+      m = fmaxf(m, ms[c]);
+    }
+    float l = 0.f;
+#pragma unroll
+    for (int c = 0; c < kInterBlockSegs; ++c) l += (ms[c] == -INFINITY) ? 0.f : ls[c] * fast_exp2((ms[c] - m) * kLog2e);
+    const float inv = 1.0f / l, mb = -m * kLog2e;
+    u32x4* yr = reinterpret_cast<u32x4*>(y + row * y_pitch);
+    for (int idx = v0 + lane; idx < v1; idx += kWave) {
+      float f[V];
+      Elem<T>::unpack(xr[idx], f);
+#pragma unroll
+      for (int i = 0; i < V; ++i) f[i] = fast_exp2(fmaf(f[i], kLog2e, mb)) * inv;
+      yr[idx] = Elem<T>::pack(f);
+    }
+  }
+}
+
 // level 0: unfused (three kernels, needs ml_buf = 2 * rows floats); 1: fused per lane;
-// 2: fused per wavefront (the shipped kernel for rows of up to 4096 values); 3: fused per workgroup (the streaming kernel).
+// 2: fused per wavefront (the shipped kernel for rows of up to 4096 values); 3: fused per workgroup (the streaming kernel);
+// 4: fused across workgroups (two kernels, needs ml_buf = 8 * rows floats).
 // bf16 only, n a multiple of 8 and at most 8192, 16-byte aligned rows.
 hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n, int64_t x_pitch,
                                 int64_t y_pitch, int level, float* ml_buf, hipStream_t s) {
@@ -410,7 +477,7 @@ hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n,
   const T* xp = (const T*)x;
   T* yp = (T*)y;
   const int64_t per_chunk = (int64_t)Elem<T>::kPerVec * kWave;
-  if (n % Elem<T>::kPerVec != 0 || n > 16 * per_chunk || level < 0 || level > 3) return hipErrorInvalidValue;
+  if (n % Elem<T>::kPerVec != 0 || n > 16 * per_chunk || level < 0 || level > 4) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)((rows + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg);
   const dim3 block(kSoftmaxWavesPerWg * kWave);
   if (level == 0) {
@@ -433,9 +500,17 @@ hipError_t launch_softmax_level(const void* x, void* y, int64_t rows, int64_t n,
     else if (nch <= 8) { RF_SOFTMAX_LEVEL_CASE(8); }
     else { RF_SOFTMAX_LEVEL_CASE(16); }
 #undef RF_SOFTMAX_LEVEL_CASE
-  } else {
+  } else if (level == 3) {
     hipLaunchKernelGGL((softmax_row_streaming_kernel<T, true>), dim3((unsigned)rows), dim3(kStreamThreads), 0, s,
                        xp, yp, rows, n, x_pitch, y_pitch);
+  } else {
+    if (ml_buf == nullptr) return hipErrorInvalidValue;
+    const int64_t units = rows * kInterBlockSegs;
+    const int64_t g4 = (units + kSoftmaxWavesPerWg - 1) / kSoftmaxWavesPerWg;
+    if (g4 > INT32_MAX) return hipErrorInvalidValue;
+    float* lb = ml_buf + rows * kInterBlockSegs;
+    hipLaunchKernelGGL((softmax_interblock_kernel<T, 0>), dim3((unsigned)g4), block, 0, s, xp, yp, ml_buf, lb, rows, (int)n, x_pitch, y_pitch);
+    hipLaunchKernelGGL((softmax_interblock_kernel<T, 1>), dim3((unsigned)g4), block, 0, s, xp, yp, ml_buf, lb, rows, (int)n, x_pitch, y_pitch);
   }
   return hipGetLastError();
 }

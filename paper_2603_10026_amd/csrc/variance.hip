@@ -11,7 +11,7 @@
 // of the expanded square vanishes).  It is associative and commutative, so the
 // same operator merges vectors, lanes, wavefronts.
 //
-// One workgroup of 4 wavefronts streams one row once.  Every lane turns each
+// One workgroup (4 wavefronts, or 16 when rows are few and long) streams one row once.  Every lane turns each
 // 128-bit vector into an exact state (two passes over 4 or 8 registers), merges
 // the four vectors of an iteration pairwise (equal counts: no division), and
 // folds the result into its running state; lanes merge through DPP / shuffles,
@@ -90,18 +90,19 @@ __device__ __forceinline__ VarState var_shfl_xor(const VarState& a, int mask) {
   return b;
 }
 
-constexpr int kVarWaves = 4;
-constexpr int kVarThreads = kVarWaves * kWave;
 constexpr int kVarUnroll = 4;  // 128-bit loads in flight per lane
 
 }  // namespace
 
-// VEC: the row base and pitch allow 128-bit loads.
-template <typename T, bool VEC>
-__global__ __launch_bounds__(kVarThreads) void variance_kernel(const T* __restrict__ x,
-                                                               float* __restrict__ mean_out,
-                                                               float* __restrict__ var_out,
-                                                               int64_t n, int64_t x_pitch) {
+// VEC: the row base and pitch allow 128-bit loads.  kVarWaves wavefronts share a row: 4 when
+// there are enough rows to fill the GPU, 16 when there are few (each row then needs more loads
+// in flight to be read at speed).
+template <typename T, bool VEC, int kVarWaves>
+__global__ __launch_bounds__(kVarWaves * kWave) void variance_kernel(const T* __restrict__ x,
+                                                                     float* __restrict__ mean_out,
+                                                                     float* __restrict__ var_out,
+                                                                     int64_t n, int64_t x_pitch) {
+  constexpr int kVarThreads = kVarWaves * kWave;
   constexpr int V = Elem<T>::kPerVec;
   __shared__ float s_n[kVarWaves], s_mean[kVarWaves], s_m2[kVarWaves];
   const int tid = threadIdx.x;
@@ -169,22 +170,18 @@ __global__ __launch_bounds__(kVarThreads) void variance_kernel(const T* __restri
 hipError_t launch_variance(const void* x, bool is_bf16, float* mean, float* var, int64_t rows,
                            int64_t n, int64_t x_pitch, bool vec_ok, hipStream_t s) {
   if (rows > INT32_MAX) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)rows), block(kVarThreads);
+  // few long rows: 16 wavefronts per row instead of 4
+  const bool wide = rows <= 512 && n >= 4096;
+  const dim3 grid((unsigned)rows), block((wide ? 16 : 4) * kWave);
+#define RF_LAUNCH_VAR(T, VEC)                                                                    \
+  if (wide) hipLaunchKernelGGL((variance_kernel<T, VEC, 16>), grid, block, 0, s, (const T*)x, mean, var, n, x_pitch); \
+  else hipLaunchKernelGGL((variance_kernel<T, VEC, 4>), grid, block, 0, s, (const T*)x, mean, var, n, x_pitch);
   if (is_bf16) {
-    if (vec_ok)
-      hipLaunchKernelGGL((variance_kernel<bf16_t, true>), grid, block, 0, s, (const bf16_t*)x, mean,
-                         var, n, x_pitch);
-    else
-      hipLaunchKernelGGL((variance_kernel<bf16_t, false>), grid, block, 0, s, (const bf16_t*)x,
-                         mean, var, n, x_pitch);
+    if (vec_ok) { RF_LAUNCH_VAR(bf16_t, true) } else { RF_LAUNCH_VAR(bf16_t, false) }
   } else {
-    if (vec_ok)
-      hipLaunchKernelGGL((variance_kernel<float, true>), grid, block, 0, s, (const float*)x, mean,
-                         var, n, x_pitch);
-    else
-      hipLaunchKernelGGL((variance_kernel<float, false>), grid, block, 0, s, (const float*)x, mean,
-                         var, n, x_pitch);
+    if (vec_ok) { RF_LAUNCH_VAR(float, true) } else { RF_LAUNCH_VAR(float, false) }
   }
+#undef RF_LAUNCH_VAR
   return hipGetLastError();
 }
 

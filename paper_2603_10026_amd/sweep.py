@@ -6,11 +6,13 @@ rf_merge_states on the decode benchmark workload for several segment counts S an
 line per S; the fastest S is the value to pass as ``num_splits`` on this GPU.
 
 ``--what fusion``: the safe-softmax cascade fused at different levels (not fused / per lane /
-per wavefront / per workgroup) for row lengths 1K..8K, 32768 rows of bf16, through
+per wavefront / per workgroup / across workgroups) for row lengths 1K..8K, 32768 rows of bf16, through
 rf_diag_softmax_level.
 
-``--what tables``: every shape of the paper's appendix tables for the further cascades (MoE
-routing R1-R8, FP8 quant + GEMM Q1-Q10, variance V1-V8), one JSON line each.
+``--what tables``: the fp32 attention workload and every shape of the paper's appendix tables for
+the further cascades (MoE routing R1-R8, FP8 quant + GEMM Q1-Q10, variance V1-V8), one JSON line
+each: the time of one call through the Python binding, and the time per call when 24 calls are
+captured in a HIP graph and replayed (the host side of a launch is then out of the number).
 
     python -m paper_2603_10026_amd.sweep [--what splits|fusion|tables] [--splits 8,16,...] [--iters 20]
 """
@@ -82,13 +84,14 @@ def fusion_sweep(iters):
     rf.load_library()
     dev = "cuda:0"
     rows, n_rot = 32768, 3
-    names = {0: "not fused (3 kernels)", 1: "fused per lane", 2: "fused per wavefront", 3: "fused per workgroup"}
+    names = {0: "not fused (3 kernels)", 1: "fused per lane", 2: "fused per wavefront", 3: "fused per workgroup",
+             4: "fused across workgroups (2 kernels)"}
     for n in (1024, 2048, 4096, 8192):
         xs = [I.softmax_inputs_device(I.SEED_BASE + 1 + 100 * r, rows, n, 2.0, "bf16", dev) for r in range(n_rot)]
         ys = [torch.empty_like(x) for x in xs]
-        ml = torch.empty(2 * rows, dtype=torch.float32, device=dev)
+        ml = torch.empty(8 * rows, dtype=torch.float32, device=dev)
         base = None
-        for level in (0, 1, 2, 3):
+        for level in (0, 1, 2, 3, 4):
             for i in range(3):
                 rf.rf_diag_softmax_level(xs[i % n_rot], ys[i % n_rot], level, ml)
             torch.cuda.synchronize()
@@ -130,6 +133,39 @@ def tables_sweep(iters):
         ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
         return ts[len(ts) // 2]
 
+    def timed_graph(fn, launches=24, replays=7):
+        """Per-call time with the host out of the picture: `launches` calls captured once in a
+        HIP graph (inputs rotating as in `timed`) and replayed; median over the replays."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(launches):
+                fn(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(replays):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / launches)
+        del graph
+        return sorted(ts)[len(ts) // 2]
+
+    c0 = I.WORKLOADS[0]
+    q, k, v = I.attention_inputs_device(I.SEED_BASE, c0["B"], c0["Hq"], c0["Hkv"], c0["Lq"], c0["Lk"], c0["d"], "f32", dev)
+    o = torch.empty_like(q)
+    f0 = lambda i: rf.rf_cascade_attention(q, k, v, I.default_scale(c0["d"]), False, o=o)
+    print(json.dumps(dict(config="C1", workload=c0["name"], us_median=round(timed(f0), 2),
+                          us_graph_replay=round(timed_graph(f0), 2))), flush=True)
+
     for key in sorted(I.MOE_ROUTING_TABLE):
         c = I.table_workload(key)
         sets = []
@@ -138,20 +174,24 @@ def tables_sweep(iters):
             sets.append((x, w, torch.empty((c["S"], c["topk"]), dtype=torch.float32, device=dev),
                          torch.empty((c["S"], c["topk"]), dtype=torch.int32, device=dev)))
         ws = torch.empty(rf.moe_routing_workspace_bytes(c["S"], c["hd"], c["E"]), dtype=torch.uint8, device=dev)
-        med = timed(lambda i: rf.rf_moe_routing(sets[i % n_rot][0], sets[i % n_rot][1], c["topk"], prob=sets[i % n_rot][2],
-                                                idx=sets[i % n_rot][3], workspace=ws))
+        fn = lambda i: rf.rf_moe_routing(sets[i % n_rot][0], sets[i % n_rot][1], c["topk"], prob=sets[i % n_rot][2],
+                                         idx=sets[i % n_rot][3], workspace=ws)
+        med, gr = timed(fn), timed_graph(fn)
         b = 2.0 * c["S"] * c["hd"] + 2.0 * c["hd"] * c["E"] + 8.0 * c["S"] * c["topk"]
-        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), algorithmic_MB=round(b / 1e6, 2),
-                              GBps=round(b / med / 1e3, 1))), flush=True)
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), us_graph_replay=round(gr, 2),
+                              algorithmic_MB=round(b / 1e6, 2), GBps=round(b / med / 1e3, 1),
+                              GBps_graph_replay=round(b / gr / 1e3, 1))), flush=True)
         del sets, ws
     for key in sorted(I.FP8_QUANT_GEMM_TABLE, key=lambda k: int(k[1:])):
         c = I.table_workload(key)
         a, w = I.fp8_quant_gemm_inputs_device(I.SEED_BASE + 7, c["M"], c["K"], c["N"], dev)
         out = torch.empty((c["M"], c["N"]), dtype=torch.bfloat16, device=dev)
-        med = timed(lambda i: rf.rf_fp8_quant_gemm(a, w, c=out))
+        fn = lambda i: rf.rf_fp8_quant_gemm(a, w, c=out)
+        med, gr = timed(fn), timed_graph(fn, launches=12)
         fl = 2.0 * c["M"] * c["K"] * c["N"]
-        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), GFLOP=round(fl / 1e9, 1),
-                              TFLOPs=round(fl / med / 1e6, 1))), flush=True)
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), us_graph_replay=round(gr, 2),
+                              GFLOP=round(fl / 1e9, 1), TFLOPs=round(fl / med / 1e6, 1),
+                              TFLOPs_graph_replay=round(fl / gr / 1e6, 1))), flush=True)
         del a, w, out
     for key in sorted(I.VARIANCE_TABLE, key=lambda k: int(k[1:])):
         c = I.table_workload(key)
@@ -159,10 +199,12 @@ def tables_sweep(iters):
               for r in range(n_rot)]
         mv = [(torch.empty(c["bs"], dtype=torch.float32, device=dev), torch.empty(c["bs"], dtype=torch.float32, device=dev))
               for _ in range(n_rot)]
-        med = timed(lambda i: rf.rf_variance(xs[i % n_rot], *mv[i % n_rot]))
+        fn = lambda i: rf.rf_variance(xs[i % n_rot], *mv[i % n_rot])
+        med, gr = timed(fn), timed_graph(fn)
         b = 4.0 * c["bs"] * c["l"] + 8.0 * c["bs"]
-        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), algorithmic_MB=round(b / 1e6, 2),
-                              GBps=round(b / med / 1e3, 1))), flush=True)
+        print(json.dumps(dict(config=key, workload=c["name"], us_median=round(med, 2), us_graph_replay=round(gr, 2),
+                              algorithmic_MB=round(b / 1e6, 2), GBps=round(b / med / 1e3, 1),
+                              GBps_graph_replay=round(b / gr / 1e3, 1))), flush=True)
         del xs, mv
     return 0
 

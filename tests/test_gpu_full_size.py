@@ -74,6 +74,18 @@ def test_workload0_attention_f32_full(rf):
     check_rows(I.to_numpy(o).reshape(-1, c["d"]), ref.reshape(-1, c["d"]), 1e-5, "attention f32, whole output", row_tol=1e-5)
 
 
+def test_workload0_batched_heads_f32_full(rf):
+    """The bench's labelled extension of workload 0 (the same shape over 16 x 32 heads)."""
+    c = W[0]
+    say("attention f32, 16 x 32 heads")
+    q, k, v = I.attention_inputs_device(I.SEED_BASE + 50, 16, 32, 32, c["Lq"], c["Lk"], c["d"], "f32", DEV)
+    sc = I.default_scale(c["d"])
+    o = rf.rf_cascade_attention(q, k, v, sc, False, o=nan_like(q.shape, q.dtype))
+    torch.cuda.synchronize()
+    ref = O.attention(I.to_numpy(q), I.to_numpy(k), I.to_numpy(v), sc, False)
+    check_rows(I.to_numpy(o).reshape(-1, c["d"]), ref.reshape(-1, c["d"]), 1e-5, "attention f32 batched, whole output", row_tol=1e-5)
+
+
 def test_workload1_softmax_full(rf):
     c = W[1]
     say(c["name"])

@@ -473,14 +473,14 @@ def test_fp8_quant_gemm_special_rows_and_pitched_output(rf):
 
 
 # ------------------------------------------- softmax fused at different levels
-@pytest.mark.parametrize("level", [0, 1, 2, 3])
+@pytest.mark.parametrize("level", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("rows,n", [(37, 512), (9, 4096), (5, 8192), (130, 1000)])
 def test_softmax_fusion_levels(rf, level, rows, n):
     say(f"softmax fusion level {level} rows={rows} n={n}")
     x = I.softmax_inputs(I.SEED_BASE + 1, rows, n, 2.0, "bf16")
     tx = I.to_torch(x, "bf16", DEV)
     ty = torch.empty_like(tx)
-    ml = torch.empty(2 * rows, dtype=torch.float32, device=DEV)
+    ml = torch.full((8 * rows,), float("nan"), dtype=torch.float32, device=DEV)
     rf.rf_diag_softmax_level(tx, ty, level, ml)
     torch.cuda.synchronize()
     check(ty, O.safe_softmax(x), "bf16", f"softmax level {level}")

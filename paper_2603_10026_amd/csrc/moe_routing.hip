@@ -49,11 +49,21 @@ __device__ __forceinline__ int fWm(int krow) { return ((krow & 3) << 2) & (PPR -
 
 }  // namespace
 
+template <int EPL>
+__device__ __forceinline__ void moe_cascade_token(const float (&p)[EPL], int q, int row, bool live,
+                                                  int topk, float* __restrict__ prob,
+                                                  int32_t* __restrict__ idx, int64_t ldp, int64_t ldi);
+
 // NT = E / 32.  part[ks][row][e] = sum over the k slice of x[row,k] w[k,e].
-template <int NT>
+// FUSED (single-segment strategy, Section 4.3: the whole contraction axis in one workgroup, grid
+// y = 1): the scores never leave the chip; the workgroup runs the cascade on them itself and
+// writes prob / idx.  Chosen when the contraction axis is short enough that splitting it only
+// buys a second launch.
+template <int NT, bool FUSED>
 __global__ __launch_bounds__(kMoeThreads) void moe_scores_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, float* __restrict__ part, int S,
-    int n_kblocks, int64_t ldx, int64_t ldw) {
+    int n_kblocks, int64_t ldx, int64_t ldw, int topk, float* __restrict__ prob,
+    int32_t* __restrict__ idx, int64_t ldp, int64_t ldi) {
   constexpr int E = 32 * NT;
   constexpr int PPR = E / 8;               // 16-byte pieces per W row
   constexpr int kWTileB = kMoeKB * E * 2;  // [k][e]
@@ -231,47 +241,66 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scores_kernel(
         }
   }
   __syncthreads();
-  float* prow = part + ((int64_t)ks * S) * E;
+  if constexpr (!FUSED) {
+    float* prow = part + ((int64_t)ks * S) * E;
 #pragma unroll
-  for (int cc = 0; cc < CPW; ++cc) {
-    const int c = wave * CPW + cc;
-    f32x4 v = red[c * 64 + lane];
+    for (int cc = 0; cc < CPW; ++cc) {
+      const int c = wave * CPW + cc;
+      f32x4 v = red[c * 64 + lane];
 #pragma unroll
-    for (int r = 1; r < 4; ++r) v += red[r * (kChunks * 64) + c * 64 + lane];
-    const int ni = c >> 3, mi = (c >> 2) & 1, r4 = c & 3;
-    const int m = row0 + 32 * mi + i32;
-    if (m < S) *reinterpret_cast<f32x4*>(prow + (int64_t)m * E + 32 * ni + 8 * r4 + 4 * hh) = v;
+      for (int r = 1; r < 4; ++r) v += red[r * (kChunks * 64) + c * 64 + lane];
+      const int ni = c >> 3, mi = (c >> 2) & 1, r4 = c & 3;
+      const int m = row0 + 32 * mi + i32;
+      if (m < S) *reinterpret_cast<f32x4*>(prow + (int64_t)m * E + 32 * ni + 8 * r4 + 4 * hh) = v;
+    }
+  } else {
+    // sums in the same fixed order, kept in registers until every wavefront has read the four
+    // copies, then laid out [token][expert] at the start of LDS
+    f32x4 sum[CPW];
+#pragma unroll
+    for (int cc = 0; cc < CPW; ++cc) {
+      const int c = wave * CPW + cc;
+      sum[cc] = red[c * 64 + lane];
+#pragma unroll
+      for (int r = 1; r < 4; ++r) sum[cc] += red[r * (kChunks * 64) + c * 64 + lane];
+    }
+    __syncthreads();
+    float* sc = reinterpret_cast<float*>(lds);  // [kMoeRows][E + 4] (padded rows)
+#pragma unroll
+    for (int cc = 0; cc < CPW; ++cc) {
+      const int c = wave * CPW + cc;
+      const int ni = c >> 3, mi = (c >> 2) & 1, r4 = c & 3;
+      *reinterpret_cast<f32x4*>(sc + (32 * mi + i32) * (E + 4) + 32 * ni + 8 * r4 + 4 * hh) = sum[cc];
+    }
+    __syncthreads();
+    // the cascade: 16 lanes per token, 16 tokens per pass
+    constexpr int EPL = E / 16;
+    const int q = tid & 15;
+#pragma unroll 1
+    for (int pass = 0; pass < kMoeRows / 16; ++pass) {
+      const int tl = 16 * pass + (tid >> 4);
+      const int row = row0 + tl;
+      float p[EPL];
+#pragma unroll
+      for (int i = 0; i < EPL; i += 2) {
+        const float2 v2 = *reinterpret_cast<const float2*>(sc + tl * (E + 4) + q * EPL + i);
+        p[i] = v2.x;
+        p[i + 1] = v2.y;
+      }
+      moe_cascade_token<EPL>(p, q, row, row < S, topk, prob, idx, ldp, ldi);
+    }
   }
 }
 
 // 16 lanes per token; lane q owns experts [q EPL, (q+1) EPL).
 constexpr int kCascadeThreads = 64;  // one wavefront = 4 tokens per workgroup
 
+// The cascade of one token on the scores p[EPL] its 16 lanes hold (lane q: experts q EPL ..).
 template <int EPL>
-__global__ __launch_bounds__(kCascadeThreads) void moe_cascade_kernel(
-    const float* __restrict__ part, int KS, int S, int topk, float* __restrict__ prob,
-    int32_t* __restrict__ idx, int64_t ldp, int64_t ldi) {
+__device__ __forceinline__ void moe_cascade_token(const float (&p)[EPL], int q, int row, bool live,
+                                                  int topk, float* __restrict__ prob,
+                                                  int32_t* __restrict__ idx, int64_t ldp, int64_t ldi) {
   constexpr int E = 16 * EPL;
-  const int tid = threadIdx.x;
-  const int q = tid & 15;
-  const int row = blockIdx.x * (kCascadeThreads / 16) + (tid >> 4);
-  const bool live = row < S;
-  const int rrow = live ? row : S - 1;  // dead groups repeat the last token, store nothing
-
-  // scores: slices added in slice order
-  float p[EPL];
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) p[i] = 0.f;
-#pragma unroll 8
-  for (int s = 0; s < KS; ++s) {
-    const float* src = part + ((int64_t)s * S + rrow) * E + q * EPL;
-#pragma unroll
-    for (int i = 0; i < EPL; i += 2) {
-      const float2 v = *reinterpret_cast<const float2*>(src + i);
-      p[i] += v.x;
-      p[i + 1] += v.y;
-    }
-  }
   // stage 1: max;  stage 2: sum of exponentials (lane-level fused form, merged across
   // the 16 lanes with the level-k expression)
   float m = p[0];
@@ -327,14 +356,32 @@ __global__ __launch_bounds__(kCascadeThreads) void moe_cascade_kernel(
   }
 }
 
-int moe_num_slices(int S, int hd) {
-  const int n_rb = (S + kMoeRows - 1) / kMoeRows;
-  const int n_kblocks = hd / kMoeKB;
-  int ks = (256 + n_rb - 1) / n_rb;  // aim at one workgroup per CU
-  if (ks > n_kblocks) ks = n_kblocks;
-  if (ks > 64) ks = 64;
-  if (ks < 1) ks = 1;
-  return ks;
+template <int EPL>
+__global__ __launch_bounds__(kCascadeThreads) void moe_cascade_kernel(
+    const float* __restrict__ part, int KS, int S, int topk, float* __restrict__ prob,
+    int32_t* __restrict__ idx, int64_t ldp, int64_t ldi) {
+  constexpr int E = 16 * EPL;
+  const int tid = threadIdx.x;
+  const int q = tid & 15;
+  const int row = blockIdx.x * (kCascadeThreads / 16) + (tid >> 4);
+  const bool live = row < S;
+  const int rrow = live ? row : S - 1;  // dead groups repeat the last token, store nothing
+
+  // scores: slices added in slice order
+  float p[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) p[i] = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < KS; ++s) {
+    const float* src = part + ((int64_t)s * S + rrow) * E + q * EPL;
+#pragma unroll
+    for (int i = 0; i < EPL; i += 2) {
+      const float2 v = *reinterpret_cast<const float2*>(src + i);
+      p[i] += v.x;
+      p[i + 1] += v.y;
+    }
+  }
+  moe_cascade_token<EPL>(p, q, row, live, topk, prob, idx, ldp, ldi);
 }
 
 // Device address of `scratch` on the current device, resolved once per device (with that
@@ -364,6 +411,23 @@ hipError_t launch_moe_routing_static(const void* x, const void* w, int S, int hd
   return launch_moe_routing(x, w, S, hd, E, topk, ldx, ldw, prob, idx, ldp, ldi, part, s);
 }
 
+// Contraction axes of at most this length are not split: one launch, scores stay on chip.
+// Measured on 2048 tokens: with only S/64 workgroups, each streaming all of w, the single
+// segment wins at hd = 768 and 1024 (by half a microsecond per call under graph replay) and
+// loses from hd = 2048 on (18 us against 11 us for 64 experts, 29 against 17.5 for 128).
+constexpr int kMoeSingleSegmentMaxHd = 1024;
+
+int moe_num_slices(int S, int hd) {
+  if (hd <= kMoeSingleSegmentMaxHd) return 1;  // (one slice is still what the workspace query promises room for)
+  const int n_rb = (S + kMoeRows - 1) / kMoeRows;
+  const int n_kblocks = hd / kMoeKB;
+  int ks = (256 + n_rb - 1) / n_rb;  // aim at one workgroup per CU
+  if (ks > n_kblocks) ks = n_kblocks;
+  if (ks > 64) ks = 64;
+  if (ks < 1) ks = 1;
+  return ks;
+}
+
 hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E, int topk,
                               int64_t ldx, int64_t ldw, float* prob, int32_t* idx, int64_t ldp,
                               int64_t ldi, float* part, hipStream_t s) {
@@ -376,10 +440,20 @@ hipError_t launch_moe_routing(const void* x, const void* w, int S, int hd, int E
   const dim3 grid1((unsigned)n_rb, (unsigned)KS), block(kMoeThreads);
   const bf16_t* xb = (const bf16_t*)x;
   const bf16_t* wb = (const bf16_t*)w;
+  if (hd <= kMoeSingleSegmentMaxHd) {
+    // single-segment strategy: scores GEMM and cascade in one kernel
+    switch (E) {
+      case 32: hipLaunchKernelGGL((moe_scores_kernel<1, true>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
+      case 64: hipLaunchKernelGGL((moe_scores_kernel<2, true>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
+      case 128: hipLaunchKernelGGL((moe_scores_kernel<4, true>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (E) {
-    case 32: hipLaunchKernelGGL((moe_scores_kernel<1>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw); break;
-    case 64: hipLaunchKernelGGL((moe_scores_kernel<2>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw); break;
-    case 128: hipLaunchKernelGGL((moe_scores_kernel<4>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw); break;
+    case 32: hipLaunchKernelGGL((moe_scores_kernel<1, false>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
+    case 64: hipLaunchKernelGGL((moe_scores_kernel<2, false>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
+    case 128: hipLaunchKernelGGL((moe_scores_kernel<4, false>), grid1, block, 0, s, xb, wb, part, S, n_kblocks, ldx, ldw, topk, prob, idx, ldp, ldi); break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();

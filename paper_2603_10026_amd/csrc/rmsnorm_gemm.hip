@@ -44,7 +44,14 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void global_cvoid;
 
 // 16-byte slot swizzles (slot = piece ^ f(row)).
-__device__ __forceinline__ int fX(int row) { return (row >> 1) & 7; }
+// X rows are 128 bytes = 8 slots.  The row bits are mixed so that both access shapes of the X
+// stage are free of bank conflicts: the 128-bit stores of the staging role (four lanes per
+// row, consecutive rows) and the 128-bit fragment reads (one row per lane).  Found by timing
+// every XOR-linear 3-bit function of the low five row bits on the GPU; (row >> 1) & 7, the
+// obvious choice, makes the stores 2-way conflicted.
+__device__ __forceinline__ int fX(int row) {
+  return ((row ^ (row >> 2)) & 1) | (((row ^ (row >> 3)) & 1) << 1) | (((row >> 1) & 1) << 2);
+}
 __device__ __forceinline__ int fW(int krow) { return (krow & 3) << 2; }
 
 }  // namespace

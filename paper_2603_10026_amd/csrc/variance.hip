@@ -170,8 +170,10 @@ __global__ __launch_bounds__(kVarWaves * kWave) void variance_kernel(const T* __
 hipError_t launch_variance(const void* x, bool is_bf16, float* mean, float* var, int64_t rows,
                            int64_t n, int64_t x_pitch, bool vec_ok, hipStream_t s) {
   if (rows > INT32_MAX) return hipErrorInvalidValue;
-  // few long rows: 16 wavefronts per row instead of 4
-  const bool wide = rows <= 512 && n >= 4096;
+  // Few long rows: 16 wavefronts per row instead of 4.  Measured per call under graph replay:
+  // 128 rows of 32768 go from 8.5 to 6.0 us, one such row from 4.2 to 3.8; rows of 8192 are
+  // faster with 4 wavefronts (2.7 against 3.2 us), and so are 512 rows or more of any length.
+  const bool wide = rows <= 256 && n >= 16384;
   const dim3 grid((unsigned)rows), block((wide ? 16 : 4) * kWave);
 #define RF_LAUNCH_VAR(T, VEC)                                                                    \
   if (wide) hipLaunchKernelGGL((variance_kernel<T, VEC, 16>), grid, block, 0, s, (const T*)x, mean, var, n, x_pitch); \

@@ -229,15 +229,27 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
   // waits (the compiler would otherwise wait for the in-flight direct-to-LDS loads
   // before every LDS access).
   float ss_done = 0.f;
+  // Fragment registers, two buffers.  They outlive a step: the 8 MFMAs of a step's last
+  // contraction step are issued only after the NEXT step's barrier, while that step's first
+  // fragment reads are on their way (their operands sit in buffer 1 across the barrier).
+  // Without this the matrix pipe idles from the barrier until the first fragments arrive,
+  // with both wavefronts of every SIMD waiting for the same thing.
+  u32x2 af[2][2][2];  // [buffer][ni][w2]
+  u32x4 bfr[2][4];    // [buffer][mi]
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int w2 = 0; w2 < 2; ++w2) af[1][ni][w2] = u32x2{0u, 0u};  // (the first step has nothing deferred:
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) bfr[1][mi] = u32x4{0u, 0u, 0u, 0u};  //  zero operands add nothing)
   auto k_step = [&](int s, auto stage_tag) {
     constexpr int ST = decltype(stage_tag)::value;  // LDS stage of this step (= s % 2)
     ss_done = ss;  // complete once s is the last step
-    // W tile s has landed; our own LDS writes of the previous step are done
+    // W tile s has landed; our own LDS writes of the previous step are done, and so are its
+    // fragment reads (buffer 1 is complete)
     asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();  // stages of step s complete; stages of step s-1 free
 
-    u32x2 af[2][2][2];  // [buffer][ni][w2]
-    u32x4 bfr[2][4];    // [buffer][mi]
     u32x4 conv;
 #define RF_ISSUE(BUFR, KK)                                                                   \
   _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) {                                         \
@@ -282,9 +294,13 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
   __builtin_amdgcn_sched_barrier(0);
 
     RF_ISSUE(0, 0)
-    RF_ISSUE(1, 1)
     // (issued while the first fragments are on their way)
     RF_ISSUE_W(min(s + 1, nk - 1), ST ^ 1)
+    // the previous step's last contraction step, out of buffer 1
+    RF_MFMA4(1, 0)
+    RF_MFMA4(1, 1)
+    __builtin_amdgcn_sched_barrier(0);
+    RF_ISSUE(1, 1)
     RF_WAIT(0, 8)
     RF_GROUP(0, 0, 0)
     RF_ISSUE(0, 2)
@@ -293,8 +309,14 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
     RF_ISSUE(1, 3)
     RF_WAIT(0, 8)
     RF_GROUP(0, 1, 0)
+    // the last contraction step: its fragments must be back before the next barrier (the stage
+    // is overwritten after it); its conversion work is done here, its MFMAs after that barrier
     RF_WAIT(1, 0)
-    RF_GROUP(1, 1, 2)
+    RF_CONVERT_PAIR(1, 2)
+    RF_CONVERT_PAIR(1, 3)
+    RF_STORE_PIECE(1, ST ^ 1)
+    RF_LOAD_PIECE(1, min(s + 2, nk - 1))
+    __builtin_amdgcn_sched_barrier(0);
 #undef RF_ISSUE
 #undef RF_WAIT
 #undef RF_MFMA4
@@ -304,6 +326,20 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
     k_step(s, std::integral_constant<int, 0>{});
     if (s + 1 < nk) k_step(s + 1, std::integral_constant<int, 1>{});
   }
+  // the last step's deferred contraction step
+#define RF_MFMA4(BUFR, NI)                                                                   \
+  {                                                                                          \
+    u32x4 a_;                                                                                \
+    a_[0] = af[BUFR][NI][0][0]; a_[1] = af[BUFR][NI][0][1];                                  \
+    a_[2] = af[BUFR][NI][1][0]; a_[3] = af[BUFR][NI][1][1];                                  \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) acc[NI][mi] =                           \
+        __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_),              \
+                                                __builtin_bit_cast(bf16x8, bfr[BUFR][mi]),   \
+                                                acc[NI][mi], 0, 0, 0);                       \
+  }
+  RF_MFMA4(1, 0)
+  RF_MFMA4(1, 1)
+#undef RF_MFMA4
   ss = ss_done;
   // (the registers of the surplus prefetch stay reserved until it has landed)
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"

@@ -72,7 +72,26 @@ def build_library(verbose=True, jobs=8):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    check_waits(verbose)
     return LIB
+
+
+def check_waits(verbose=True):
+    """Kernels that load registers from inline assembly and count their own waits are
+    checked against a model of the vector-memory counter (see check_isa); a register touched
+    while its load is in flight fails the build."""
+    from . import check_isa
+    cc = hipcc()
+    for src in SOURCES:
+        path = os.path.join(CSRC, src)
+        if not check_isa.uses_asm_loads(path):
+            continue
+        n, hazards = check_isa.check_source(path, cc, HIPCC_FLAGS)
+        if verbose:
+            print(f"check_isa {src}: {n} kernels, {len(hazards)} hazards", flush=True)
+        if hazards:
+            raise RuntimeError(f"{src}: registers touched while their loads are in flight:\n  "
+                               + "\n  ".join(hazards[:20]))
 
 
 def _drain(procs):

@@ -1,0 +1,165 @@
+"""Build-time check of the hand-counted vector-memory waits.
+
+Some kernels issue ``global_load_dwordx4`` into registers from inline assembly and wait for
+the data with ``s_waitcnt vmcnt(N)`` statements written by hand, many instructions later.
+The compiler sees each such statement as an ordinary definition of the destination
+registers: it inserts no wait of its own, and nothing stops its register allocator from
+copying or spilling a destination while the load is still in flight (a copy at a loop's
+back edge, where the two unrolled halves of a pipeline chose different registers, is the
+case that has been seen).  Such a copy reads the register's old contents and the kernel
+computes garbage with no error.
+
+This module compiles a source to gfx950 assembly (device code only) and walks each kernel
+with a model of the in-order vector-memory counter: every vector-memory instruction joins a
+queue, ``s_waitcnt vmcnt(N)`` retires all but the newest N, and an instruction that names a
+register that a queued load will still write is reported.  The walk follows the text from
+top to bottom and then takes each backward branch once more from its target with the queue
+it had at the branch, which covers the steady state of a software-pipelined loop.  Forward
+branches are taken as falling through; that is exact for the kernels checked here, whose
+loops hold no divergent control flow between a load and its wait.
+
+``python -m paper_2603_10026_amd.check_isa file.hip [...]`` prints what it finds and exits
+non-zero on a hazard.
+"""
+from __future__ import annotations
+
+import os
+import re
+import subprocess
+import sys
+import tempfile
+
+_VM_PREFIX = ("global_load", "global_store", "global_atomic", "buffer_load", "buffer_store",
+              "buffer_atomic", "flat_load", "flat_store", "flat_atomic", "scratch_load",
+              "scratch_store")
+_REG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+_LABEL = re.compile(r"^([.\w$]+):")
+_VMCNT = re.compile(r"vmcnt\((\d+)\)")
+_BRANCH = re.compile(r"^s_c?branch\w*\s+([.\w$]+)")
+
+
+def _regs(text):
+    out = set()
+    for m in _REG.finditer(text):
+        if m.group(1) is not None:
+            out.add(int(m.group(1)))
+        else:
+            out.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
+
+def _parse(asm_text):
+    """Split an assembly file into kernels: name -> list of (kind, payload) entries."""
+    kernels = {}
+    cur = None
+    for raw in asm_text.splitlines():
+        line = raw.split(";")[0].rstrip()
+        if not line.strip():
+            continue
+        m = _LABEL.match(line)
+        if m:
+            name = m.group(1)
+            if not name.startswith(".L"):
+                cur = kernels.setdefault(name, [])
+            elif cur is not None:
+                cur.append(("label", name))
+            continue
+        s = line.strip()
+        if s.startswith(".") or cur is None:
+            if s.startswith(".end_amdhsa_kernel") or s.startswith(".Lfunc_end"):
+                cur = None
+            continue
+        if s.startswith("s_endpgm"):
+            cur.append(("ins", s))
+            continue
+        cur.append(("ins", s))
+    return {k: v for k, v in kernels.items() if any(e[1].startswith("s_endpgm") for e in v if e[0] == "ins")}
+
+
+def _step(ins, queue, where, report):
+    """Apply one instruction to the queue of in-flight vector-memory operations."""
+    mnem, _, ops = ins.partition(" ")
+    if mnem == "s_waitcnt":
+        m = _VMCNT.search(ops)
+        if m:
+            keep = int(m.group(1))
+            del queue[: max(0, len(queue) - keep)]
+        return
+    named = _regs(ops)
+    for dest, issued in queue:
+        hit = named & dest
+        if hit:
+            report.append(f"{where}: `{ins}` names v{min(hit)} while `{issued}` is in flight")
+            break
+    if mnem.startswith(_VM_PREFIX):
+        dest = set()
+        if "_load" in mnem and not re.search(r"\blds\b", ops) and "_lds_" not in mnem:
+            dest = _regs(ops.split(",")[0])
+        elif "atomic" in mnem and re.search(r"\b(sc0|glc)\b", ops):
+            dest = _regs(ops.split(",")[0])
+        queue.append((dest, ins))
+
+
+def check_kernel(name, entries):
+    """Return the list of hazards found in one kernel."""
+    report = []
+    labels = {p: i for i, (k, p) in enumerate(entries) if k == "label"}
+    queue = []
+    at_branch = []
+    for i, (kind, p) in enumerate(entries):
+        if kind != "ins":
+            continue
+        m = _BRANCH.match(p)
+        if m and m.group(1) in labels and labels[m.group(1)] < i:
+            at_branch.append((labels[m.group(1)], i, list(queue)))
+        _step(p, queue, f"{name} +{i}", report)
+    for start, end, q in at_branch:
+        q = list(q)
+        for i in range(start, end):
+            kind, p = entries[i]
+            if kind == "ins":
+                _step(p, q, f"{name} +{i} (second trip)", report)
+    seen, out = set(), []
+    for r in report:
+        key = r.split(": ", 1)[1]
+        if key not in seen:
+            seen.add(key)
+            out.append(r)
+    return out
+
+
+def check_text(asm_text):
+    hazards = []
+    kernels = _parse(asm_text)
+    for name, entries in kernels.items():
+        hazards += check_kernel(name, entries)
+    return len(kernels), hazards
+
+
+def check_source(path, hipcc, flags):
+    """Compile one HIP source to device assembly and check every kernel in it."""
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "dev.s")
+        cmd = [hipcc, *flags, "--cuda-device-only", "-S", path, "-o", out]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {path}:\n{r.stdout}")
+        with open(out) as f:
+            return check_text(f.read())
+
+
+def uses_asm_loads(path):
+    with open(path) as f:
+        return re.search(r'asm[^;]*"global_load_dwordx\d %0', f.read()) is not None
+
+
+if __name__ == "__main__":
+    from . import build as _b
+    bad = 0
+    for src in sys.argv[1:]:
+        n, hz = check_source(src, _b.hipcc(), _b.HIPCC_FLAGS)
+        print(f"{src}: {n} kernels, {len(hz)} hazards")
+        for h in hz:
+            print("  " + h)
+        bad += len(hz)
+    sys.exit(1 if bad else 0)

@@ -1,0 +1,76 @@
+"""The build-time model of the vector-memory counter: planted hazards are found, waits of
+the right depth clear them, and the shipped kernels that count their own waits are clean."""
+import os
+
+import pytest
+
+from paper_2603_10026_amd import build as B
+from paper_2603_10026_amd import check_isa as C
+
+HEAD = "kern:\n"
+TAIL = "\ts_endpgm\n.Lfunc_end0:\n"
+
+
+def hazards(body):
+    n, hz = C.check_text(HEAD + body + TAIL)
+    assert n == 1
+    return hz
+
+
+def test_register_read_before_its_wait_is_reported():
+    body = ("\tglobal_load_dwordx4 v[4:7], v1, s[2:3] offset:16\n"
+            "\tv_add_f32_e32 v9, v5, v5\n"
+            "\ts_waitcnt vmcnt(0)\n")
+    hz = hazards(body)
+    assert len(hz) == 1 and "v5" in hz[0]
+
+
+def test_wait_of_the_right_depth_clears_the_oldest_load_only():
+    body = ("\tglobal_load_dwordx4 v[4:7], v1, s[2:3]\n"
+            "\tglobal_load_dwordx4 v[8:11], v1, s[2:3] offset:16\n"
+            "\tglobal_load_lds_dwordx4 v[2:3], off\n"
+            "\ts_waitcnt vmcnt(2) lgkmcnt(0)\n"
+            "\tv_mov_b32_e32 v20, v4\n")
+    assert hazards(body) == []
+    assert len(hazards(body + "\tv_mov_b32_e32 v21, v8\n")) == 1
+    assert hazards(body + "\ts_waitcnt vmcnt(1)\n\tv_mov_b32_e32 v21, v8\n") == []
+
+
+def test_copy_at_a_loop_back_edge_is_reported_on_the_second_trip():
+    # the load issued late in the body is waited for at the top of the next trip, but a
+    # register copy sits between the load and the branch
+    body = (".LBB0_1:\n"
+            "\ts_waitcnt vmcnt(0)\n"
+            "\tv_add_f32_e32 v9, v4, v4\n"
+            "\tglobal_load_dwordx4 v[12:15], v1, s[2:3]\n"
+            "\tv_mov_b64_e32 v[4:5], v[12:13]\n"
+            "\ts_cbranch_scc1 .LBB0_1\n")
+    hz = hazards(body)
+    assert len(hz) == 1 and "v_mov_b64" in hz[0]
+    clean = body.replace("\tv_mov_b64_e32 v[4:5], v[12:13]\n", "")
+    assert hazards(clean) == []
+    # a read at the top of the loop, ahead of the wait, is only reachable round the back edge
+    late = body.replace("\tv_mov_b64_e32 v[4:5], v[12:13]\n", "").replace(
+        ".LBB0_1:\n", ".LBB0_1:\n\tv_mul_f32_e32 v30, v13, v13\n")
+    hz = hazards(late)
+    assert len(hz) == 1 and "second trip" in hz[0]
+
+
+def test_direct_to_lds_loads_and_stores_count_but_own_no_registers():
+    body = ("\tglobal_load_lds_dwordx4 v[2:3], off\n"
+            "\tglobal_store_dwordx4 v1, v[4:7], s[2:3]\n"
+            "\tv_mov_b32_e32 v2, 0\n"
+            "\tv_mov_b32_e32 v4, 0\n")
+    assert hazards(body) == []
+
+
+def test_sources_with_hand_counted_loads_are_found_and_clean():
+    checked = [s for s in B.SOURCES if C.uses_asm_loads(os.path.join(B.CSRC, s))]
+    assert set(checked) == {"rmsnorm_gemm.hip", "fp8_quant_gemm.hip"}
+    try:
+        cc = B.hipcc()
+    except RuntimeError:
+        pytest.skip("hipcc not found")
+    for s in checked:
+        n, hz = C.check_source(os.path.join(B.CSRC, s), cc, B.HIPCC_FLAGS)
+        assert n >= 1 and hz == [], (s, hz[:5])

@@ -62,11 +62,12 @@ __device__ __forceinline__ void wait_vmem_all() {
 
 }  // namespace
 
-template <int D, int NW>
+template <int D, int NW, bool PAIRED>
 __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     bf16_t* __restrict__ o, Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so, int Hq, int Hkv,
     int Lq, int Lk, float scale_log2e, int causal, int n_qtiles) {
+  constexpr bool paired = PAIRED;
   constexpr int KS = D / 16;                 // contraction steps of S^T = K Q^T
   constexpr int DT = D / 32;                 // 32-row tiles of O^T
   constexpr int P = D / 8;                   // 16-byte slots per K/V row
@@ -90,61 +91,38 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
   // then share that head's K/V in one L2.
   //  - no mask: head-major inside the XCD, so all query tiles of a head run together and
   //    each K/V tile is fetched into the L2 once;
-  //  - causal mask: query-tile-major, heaviest first.  The late query tiles see the most
-  //    keys; starting all of them before any light tile keeps the tail of the launch short.
+  //  - causal mask, one tile per workgroup: query-tile-major, heaviest first.  The late query
+  //    tiles see the most keys; starting all of them before any light tile keeps the tail of
+  //    the launch short;
+  //  - causal mask, two tiles per workgroup (PAIRED): all workgroups are equally heavy, so the
+  //    head-major order of the unmasked case applies.
   int qt, bh;
-  const int n_bh = gridDim.x / n_qtiles;
+  const int n_units = paired ? n_qtiles / 2 : n_qtiles;  // workgroups per head
+  const int n_bh = gridDim.x / n_units;
   if ((n_bh & 7) == 0) {
     const int hx = n_bh >> 3;            // heads per XCD
     const int xcd = blockIdx.x & 7;
     const int j = blockIdx.x >> 3;       // arrival order inside the XCD
-    if (causal) {
+    if (causal && !paired) {
       qt = n_qtiles - 1 - j / hx;
       bh = xcd * hx + j % hx;
     } else {
-      qt = j % n_qtiles;
-      bh = xcd * hx + j / n_qtiles;
+      qt = j % n_units;
+      bh = xcd * hx + j / n_units;
     }
   } else {
-    qt = n_qtiles - 1 - (int)(blockIdx.x / n_bh);
+    qt = n_units - 1 - (int)(blockIdx.x / n_bh);
     bh = blockIdx.x % n_bh;
   }
   const int h = bh % Hq;
   const int b = bh / Hq;
   const int hk = h / (Hq / Hkv);
-  const int q0 = qt * kBQ;
-
   const bf16_t* qb = q + (int64_t)b * sq.b + (int64_t)h * sq.h;
   const bf16_t* kb = k + (int64_t)b * sk.b + (int64_t)hk * sk.h;
   const bf16_t* vb = v + (int64_t)b * sv.b + (int64_t)hk * sv.h;
 
-  // Q^T fragments: slot (hh, e) of step kk stands for d = 16kk + 8hh + e
-  const int my_q = q0 + wave * 32 + i32;
-  u32x4 qf[KS];
-  {
-    const bf16_t* qp = qb + (int64_t)min(my_q, Lq - 1) * sq.l + 8 * hh;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const u32x4*>(qp + 16 * kk);
-  }
-  // The loop below needs a positive scale (row max taken on raw scores, masked
-  // scores set to -inf before scaling): fold the sign of the scale into Q, and
-  // turn scale == 0 (uniform weights) into Q = 0 with scale 1.
-  if (scale_log2e < 0.f) {
-    scale_log2e = -scale_log2e;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) qf[kk] ^= 0x80008000u;
-  } else if (scale_log2e == 0.f) {
-    scale_log2e = 1.0f;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) qf[kk] = u32x4{0u, 0u, 0u, 0u};
-  }
-
-  const int shift = Lk - Lq;
-  const int my_last = causal ? min(Lk - 1, my_q + shift) : Lk - 1;
-  const int wave_min_last = causal ? min(Lk - 1, q0 + wave * 32 + shift) : Lk - 1;
-  const int wave_last = causal ? min(Lk - 1, min(Lq - 1, q0 + wave * 32 + 31) + shift) : Lk - 1;
-  const int wg_last = causal ? min(Lk - 1, min(Lq - 1, q0 + kBQ - 1) + shift) : Lk - 1;
-  const int n_ktiles = wg_last >= 0 ? wg_last / kBK + 1 : 0;
+  const bool scale_negative = scale_log2e < 0.f, scale_zero = scale_log2e == 0.f;
+  scale_log2e = scale_zero ? 1.0f : fabsf(scale_log2e);
 
   // ---- direct-to-LDS load geometry: this lane's row / slot in each of its loads ----
   int ld_row[LD_PER_WAVE];
@@ -223,17 +201,53 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
       }
   }
 
+  const uint32_t lds_base =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+#pragma unroll
+  for (int t = 0; t < DT; ++t) { voff[t][0] += lds_base; voff[t][1] += lds_base; }
+
+  // Under a causal mask a workgroup may own two query tiles of its head, the one that sees the
+  // most keys paired with the one that sees the fewest and so on inwards: every workgroup of the
+  // launch then does the same amount of work.
+#pragma nounroll
+  for (int pass = 0; pass < (PAIRED ? 2 : 1); ++pass) {
+  if (pass) {
+    qt = n_qtiles - 1 - qt;
+    __syncthreads();  // the last tile of the first pass has been read by every wavefront
+  }
+  const int q0 = qt * kBQ;
+  // Q^T fragments: slot (hh, e) of step kk stands for d = 16kk + 8hh + e
+  const int my_q = q0 + wave * 32 + i32;
+  u32x4 qf[KS];
+  {
+    const bf16_t* qp = qb + (int64_t)min(my_q, Lq - 1) * sq.l + 8 * hh;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const u32x4*>(qp + 16 * kk);
+  }
+  // The loop below needs a positive scale (row max taken on raw scores, masked
+  // scores set to -inf before scaling): fold the sign of the scale into Q, and
+  // turn scale == 0 (uniform weights) into Q = 0 with scale 1.
+  if (scale_negative) {
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] ^= 0x80008000u;
+  } else if (scale_zero) {
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = u32x4{0u, 0u, 0u, 0u};
+  }
+
+  const int shift = Lk - Lq;
+  const int my_last = causal ? min(Lk - 1, my_q + shift) : Lk - 1;
+  const int wave_min_last = causal ? min(Lk - 1, q0 + wave * 32 + shift) : Lk - 1;
+  const int wave_last = causal ? min(Lk - 1, min(Lq - 1, q0 + wave * 32 + 31) + shift) : Lk - 1;
+  const int wg_last = causal ? min(Lk - 1, min(Lq - 1, q0 + kBQ - 1) + shift) : Lk - 1;
+  const int n_ktiles = wg_last >= 0 ? wg_last / kBK + 1 : 0;
+
   float m_ref = -INFINITY, l = 0.f;
   f32x16 acc[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-
-  const uint32_t lds_base =
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
-#pragma unroll
-  for (int t = 0; t < DT; ++t) { voff[t][0] += lds_base; voff[t][1] += lds_base; }
 
   // One key tile.  BUF is a compile-time constant so that every LDS access of the
   // tile is a loop-invariant register plus an immediate offset.
@@ -404,27 +418,48 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
         *reinterpret_cast<u32x2*>(op + 32 * t + 8 * r4 + 4 * hh) = w;
       }
   }
+  }  // pass
 }
 
 hipError_t launch_attention_bf16(const void* q, const void* k, const void* v, void* o, Strides4 sq,
                                  Strides4 sk, Strides4 sv, Strides4 so, const AttnShape& a,
                                  hipStream_t s) {
-  // Without a mask the larger workgroup wins (fewer loads per MFMA); under a causal mask the
-  // smaller one does (finer tiles balance better and waste less on the diagonal).
-  const int nw = (a.causal || a.Lq <= 128) ? 4 : 8;
-  const int bq = 32 * nw;
-  const int n_qtiles = (a.Lq + bq - 1) / bq;
-  const int64_t grid = (int64_t)n_qtiles * a.B * a.Hq;
+  // Without a mask the larger workgroup wins (fewer loads per MFMA).  Under a causal mask the
+  // query tiles of a head see different numbers of keys; a launch with enough heads gives
+  // every workgroup two tiles of one head, the heaviest with the lightest and so on inwards,
+  // so that all workgroups do the same work: with 256-query tiles if that still leaves one
+  // workgroup per compute unit, else with 128-query tiles if that leaves two.  Smaller causal
+  // launches keep one 128-query tile per workgroup, heaviest tiles first.
+  const int64_t n_bh = (int64_t)a.B * a.Hq;
+  auto tiles = [&](int bq) { return (a.Lq + bq - 1) / bq; };
+  int nw = a.Lq <= 128 ? 4 : 8;
+  int paired = 0;
+  if (a.causal) {
+    if (nw == 8 && tiles(256) % 2 == 0 && (tiles(256) / 2) * n_bh >= 256) {
+      paired = 1;
+    } else {
+      nw = 4;
+      paired = (tiles(128) % 2 == 0 && (tiles(128) / 2) * n_bh >= 512) ? 1 : 0;
+    }
+  }
+  const int n_qtiles = tiles(32 * nw);
+  const int64_t grid = (paired ? n_qtiles / 2 : n_qtiles) * n_bh;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
   const float sl2 = a.scale * kLog2e;
-#define RF_LAUNCH_ATTN(DD, NWW)                                                                   \
-  hipLaunchKernelGGL((attention_bf16_kernel<DD, NWW>), dim3((unsigned)grid), dim3(NWW * kWave), 0, s, \
+#define RF_LAUNCH_ATTN(DD, NWW, PP)                                                               \
+  hipLaunchKernelGGL((attention_bf16_kernel<DD, NWW, PP>), dim3((unsigned)grid), dim3(NWW * kWave), 0, s, \
                      (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, sq, sk, sv, so, \
                      a.Hq, a.Hkv, a.Lq, a.Lk, sl2, a.causal, n_qtiles)
   if (a.d == 128) {
-    if (nw == 4) RF_LAUNCH_ATTN(128, 4); else RF_LAUNCH_ATTN(128, 8);
+    if (paired && nw == 8) RF_LAUNCH_ATTN(128, 8, true);
+    else if (paired) RF_LAUNCH_ATTN(128, 4, true);
+    else if (nw == 4) RF_LAUNCH_ATTN(128, 4, false);
+    else RF_LAUNCH_ATTN(128, 8, false);
   } else if (a.d == 64) {
-    if (nw == 4) RF_LAUNCH_ATTN(64, 4); else RF_LAUNCH_ATTN(64, 8);
+    if (paired && nw == 8) RF_LAUNCH_ATTN(64, 8, true);
+    else if (paired) RF_LAUNCH_ATTN(64, 4, true);
+    else if (nw == 4) RF_LAUNCH_ATTN(64, 4, false);
+    else RF_LAUNCH_ATTN(64, 8, false);
   } else {
     return hipErrorInvalidValue;
   }

@@ -164,6 +164,12 @@ ATTN_CASES = [
     ("bf16", 1, 1, 1, 300, 5, 128, False),      # a single, mostly empty key tile
     ("bf16", 1, 8, 8, 384, 320, 128, False),    # 8 heads: one head per XCD in the tile order
     ("bf16", 1, 8, 8, 384, 320, 128, True),
+    # causal launches with enough heads pair a heavy and a light query tile per workgroup
+    ("bf16", 1, 128, 16, 1000, 1300, 128, True),   # pairs of 256-query tiles, ragged last tile, Lk > Lq
+    ("bf16", 1, 128, 8, 1024, 1100, 64, True),     # the same for head dimension 64
+    ("bf16", 1, 176, 8, 700, 700, 128, True),      # pairs of 128-query tiles (odd count of 256-query tiles)
+    ("bf16", 1, 176, 8, 768, 768, 64, True),
+    ("bf16", 1, 128, 16, 1024, 600, 128, True),    # Lk < Lq: the light tile of each pair sees no key
 ]
 
 

@@ -7,11 +7,13 @@
 // their codes and are only rescaled.  The result returned is acc * m / MAX, which
 // approximates a @ w^T.  The weights arrive in FP8, as w[N,K] (row n = output channel n).
 //
-// Tiling.  One workgroup of 8 wavefronts owns a 128 (m) x 512 (n) output tile and walks K
-// in steps of 128 (one barrier per step).  The product is computed transposed,
+// Tiling.  One workgroup of 8 wavefronts owns a 128 (m) x 512 (n) output tile (128 x 256 when
+// that tiling still fits the chip in one round of workgroups: shapes with few output tiles
+// then occupy up to twice as many compute units) and walks K in steps of 128 (one barrier per
+// step).  The product is computed transposed,
 // C^T = W A_q^T, with v_mfma_f32_32x32x64_f8f6f4 (FP8 x FP8, fp32 accumulate), so each
 // accumulator lane owns one token (one rescale factor per lane).
-//   A operand = W rows: every wavefront streams ITS OWN 64 output channels HBM -> LDS with
+//   A operand = W rows: every wavefront streams ITS OWN 64 (or 32) output channels HBM -> LDS with
 //               direct-to-LDS 128-bit loads into a private ring of three 64-k slots; no
 //               other wavefront reads them, so no barrier guards them.
 //   B operand = quantised tokens: a tile of `a` is loaded into registers one step ahead,
@@ -29,14 +31,21 @@ namespace {
 
 constexpr int kQWaves = 8;
 constexpr int kQThreads = kQWaves * kWave;
-constexpr int kQM = 128, kQN = 512, kQK = 128;  // K step in elements = bytes of FP8
+constexpr int kQM = 128, kQK = 128;              // K step in elements = bytes of FP8
 constexpr int kQXStageB = kQM * kQK;             // 16 KB: [m][k] bytes, 128-byte rows
-constexpr int kQWSlotB = 64 * 64;                // 4 KB: one wavefront's [64 n][64 k]
-constexpr int kQWRingB = 3 * kQWSlotB;           // per wavefront
-constexpr int kQWBase = 0;
-constexpr int kQXBase = kQWaves * kQWRingB;      // 96 KB
-constexpr int kQCorrBase = kQXBase + 2 * kQXStageB;
-constexpr int kQLdsB = kQCorrBase + 2 * kQM * 4 + kQM * 4;  // + 2 stages of factors + final maxima
+// A wavefront owns NI blocks of 32 output channels: the N tile of a workgroup is 256 NI wide.
+template <int NI>
+struct QLayout {
+  static constexpr int kN = 256 * NI;
+  static constexpr int kWaveN = 32 * NI;              // channels per wavefront
+  static constexpr int kWSlotB = kWaveN * 64;         // one wavefront's [channels][64 k]
+  static constexpr int kWRingB = 3 * kWSlotB;         // per wavefront
+  static constexpr int kWLoads = 2 * NI;              // direct-to-LDS loads per 64-k weight tile
+  static constexpr int kWBase = 0;
+  static constexpr int kXBase = kQWaves * kWRingB;    // 48 or 96 KB
+  static constexpr int kCorrBase = kXBase + 2 * kQXStageB;
+  static constexpr int kLdsB = kCorrBase + 2 * kQM * 4 + kQM * 4;  // + 2 stages of factors + final maxima
+};
 constexpr float kE4M3Max = 448.0f;
 
 // 16-byte slot swizzles
@@ -52,14 +61,19 @@ __device__ __forceinline__ int fQW(int row) { return (row >> 2) & 3; }  // 4 slo
 
 }  // namespace
 
+template <int NI>
 __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     const bf16_t* __restrict__ a, const unsigned char* __restrict__ w, bf16_t* __restrict__ c, int M,
     int K, int N, int64_t lda, int64_t ldw, int64_t ldc, int n_ntiles) {
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[kQLdsB];
+  using L = QLayout<NI>;
+  constexpr int kQN = L::kN, kQWSlotB = L::kWSlotB, kQWRingB = L::kWRingB, kQWBase = L::kWBase;
+  constexpr int kQXBase = L::kXBase, kQCorrBase = L::kCorrBase, kWL = L::kWLoads;
+  constexpr int kA1 = (NI == 2) ? 2 : 0;  // LDS reads of the second channel block's operand
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[L::kLdsB];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;  // = 64-channel block of the N tile
+  const int wave = tid >> 6;  // = channel block (32 NI wide) of the N tile
   const int i32 = lane & 31;
   const int hh = lane >> 5;
 
@@ -105,20 +119,20 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   float* s_corr = reinterpret_cast<float*>(lds + kQCorrBase);          // [2][128]
   float* s_mfinal = reinterpret_cast<float*>(lds + kQCorrBase) + 2 * kQM;  // [128]
 
-  // ---- weight role: 4 direct-to-LDS loads per wavefront per 64-k tile, 16 channels each ----
-  uint32_t wsrc_off[4];  // byte offset from w + (64-k tile) * 64
+  // ---- weight role: 2 NI direct-to-LDS loads per wavefront per 64-k tile, 16 channels each ----
+  uint32_t wsrc_off[kWL];  // byte offset from w + (64-k tile) * 64
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int row = 16 * e + (lane >> 2);  // channel inside the wavefront's 64
+  for (int e = 0; e < kWL; ++e) {
+    const int row = 16 * e + (lane >> 2);  // channel inside the wavefront's block
     const int piece = (lane & 3) ^ fQW(row);
-    const int n = min(n0 + 64 * wave + row, N - 1);
+    const int n = min(n0 + L::kWaveN * wave + row, N - 1);
     wsrc_off[e] = (uint32_t)((int64_t)n * ldw + 16 * piece);
   }
   const uint32_t wring = __builtin_amdgcn_readfirstlane(lds_base + kQWBase + wave * kQWRingB);
 #define RF_ISSUE_W(TILE, SLOT)                                                                \
   {                                                                                           \
     const char* wt_ = reinterpret_cast<const char*>(w) + (int64_t)(TILE) * 64;                \
-    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+    _Pragma("unroll") for (int e = 0; e < kWL; ++e) {                                         \
       const uint32_t dst_ = wring + (SLOT) * kQWSlotB + e * 1024;                             \
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"            \
                    :                                                                          \
@@ -138,18 +152,18 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     for (int h2 = 0; h2 < 2; ++h2)
       xaddr[kk][h2] = lds_base + kQXBase + i32 * 128 + (((4 * kk + 2 * hh + h2) ^ fQX(i32)) << 4);
   // A operand (weights): row 32 ni + i32 of the slot, slots 2 hh + {0, 1}
-  uint32_t waddr[2][2];  // [ni][half] in slot 0
+  uint32_t waddr[NI][2];  // [ni][half] in slot 0
 #pragma unroll
-  for (int ni = 0; ni < 2; ++ni)
+  for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
     for (int h2 = 0; h2 < 2; ++h2) {
       const int row = 32 * ni + i32;
       waddr[ni][h2] = wring + row * 64 + (((2 * hh + h2) ^ fQW(row)) << 4);
     }
 
-  f32x16 acc[2][4];  // [ni][mi]: C^T tile (rows = channels, columns = tokens)
+  f32x16 acc[NI][4];  // [ni][mi]: C^T tile (rows = channels, columns = tokens)
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -233,14 +247,15 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   // registers and weight tiles 2s+3, 2s+4 into the slots just read.  Every step is the same
   // straight-line code: past the end of K the prefetches re-read the last tile (nothing
   // consumes it) and the running maximum is taken from a snapshot made before the surplus
-  // quantisation.  Vector-memory issue order per step: X0, X1, W(2s+3) x4, X2, X3, W(2s+4) x4.
+  // quantisation.  Vector-memory issue order per step: X0, X1, W(2s+3), X2, X3, W(2s+4), where a
+  // weight tile is kWL loads.
   int wslot = 0;
   for (int s = 0; s < nk; ++s) {
     const int st = s & 1;
     m_done = m_run;  // complete once s is the last step
-    // Weight tile 2s has landed: 12 younger loads (W(2s+1), X x4, W(2s+2)) may still fly.
+    // Weight tile 2s has landed: the younger loads (W(2s+1), X x4, W(2s+2)) may still fly.
     // Our own LDS writes of the previous step are done.
-    asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * kWL + 4) : "memory");
     __builtin_amdgcn_s_barrier();  // token stage st and its factors are complete; stage st^1 is free
 
     const uint32_t xst = st * kQXStageB;
@@ -288,17 +303,19 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   }
 #define RF_FENCE __builtin_amdgcn_sched_barrier(0);
 
-    // fragments of weight tile 2s: 12 x 128 bits, in the order of their first use
+    // fragments of weight tile 2s: 10 + kA1 x 128 bits, in the order of their first use
     RF_READ_A(a0, 0, 0)
     RF_READ_B(b0, 0, 0) RF_READ_B(b1, 1, 0) RF_READ_B(b2, 2, 0) RF_READ_B(b3, 3, 0)
-    RF_READ_A(a1, 1, 0)
-    // the factors (issued first) are back once at most the 12 fragment reads are in flight
-    asm volatile("s_waitcnt lgkmcnt(12)" : "+v"(corr[0]), "+v"(corr[1]), "+v"(corr[2]), "+v"(corr[3]));
+    if constexpr (NI == 2) { RF_READ_A(a1, 1, 0) }
+    // the factors (issued first) are back once at most the fragment reads are in flight
+    asm volatile("s_waitcnt lgkmcnt(%4)"
+                 : "+v"(corr[0]), "+v"(corr[1]), "+v"(corr[2]), "+v"(corr[3])
+                 : "n"(10 + kA1));
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
       if (__builtin_amdgcn_ballot_w64(corr[mi] != 1.0f) != 0) {  // a maximum moved: rescale (uniform)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[ni][mi][r] *= corr[mi];
       }
@@ -306,70 +323,72 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     RF_FENCE
 
     // ---- weight tile 2s ----
-    RF_WAIT2(a0, b0, 8)
+    RF_WAIT2(a0, b0, 6 + kA1)
     RF_MFMA(0, 0, a0, b0)
-    RF_WAIT_X2(0, 1, 10)  // token pieces 0, 1 of tile s+1: W(2s+1), X2, X3, W(2s+2) may still fly
+    RF_WAIT_X2(0, 1, 2 * kWL + 2)  // token pieces 0, 1 of tile s+1: W(2s+1), X2, X3, W(2s+2) may still fly
     amax_bits = __builtin_bit_cast(unsigned, __builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])));
     RF_FENCE
-    RF_WAIT1(b1, 6)
+    RF_WAIT1(b1, 4 + kA1)
     RF_MFMA(0, 1, a0, b1)
-    RF_WAIT_X2(2, 3, 4)  // pieces 2, 3: W(2s+2) may still fly
+    RF_WAIT_X2(2, 3, kWL)  // pieces 2, 3: W(2s+2) may still fly
     amax = fold_max(__builtin_elementwise_max(
         __builtin_bit_cast(u16x2, amax_bits), __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
     update_max(st ^ 1);
     RF_FENCE
-    RF_WAIT1(b2, 4)
+    RF_WAIT1(b2, 2 + kA1)
     RF_MFMA(0, 2, a0, b2)
     RF_FENCE
-    RF_WAIT1(b3, 2)
+    RF_WAIT1(b3, kA1)
     RF_MFMA(0, 3, a0, b3)
     RF_FENCE
-    RF_WAIT1(a1, 0)  // every read of ring slot wslot is back
+    if constexpr (NI == 2) { RF_WAIT1(a1, 0) }  // every read of ring slot wslot is back
     RF_QUANT_STORE(0, st ^ 1)
     RF_LOAD_X(0, min(s + 2, nk - 1))
     RF_QUANT_STORE(1, st ^ 1)
     RF_LOAD_X(1, min(s + 2, nk - 1))
     RF_READ_A(a0, 0, 1)       // first operand of weight tile 2s+1
-    RF_MFMA(1, 0, a1, b0)
+    if constexpr (NI == 2) { RF_MFMA(1, 0, a1, b0) }
     RF_READ_B(b0, 0, 1)
     RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)  // refill the slot just read
     RF_FENCE
-    RF_MFMA(1, 1, a1, b1)
+    if constexpr (NI == 2) { RF_MFMA(1, 1, a1, b1) }
     RF_READ_B(b1, 1, 1)
     RF_FENCE
-    RF_MFMA(1, 2, a1, b2)
+    if constexpr (NI == 2) { RF_MFMA(1, 2, a1, b2) }
     RF_READ_B(b2, 2, 1)
     RF_FENCE
-    RF_MFMA(1, 3, a1, b3)
+    if constexpr (NI == 2) { RF_MFMA(1, 3, a1, b3) }
     RF_READ_B(b3, 3, 1)
-    RF_READ_A(a1, 1, 1)
+    if constexpr (NI == 2) { RF_READ_A(a1, 1, 1) }
     RF_FENCE
 
     // ---- weight tile 2s+1 ----
-    // LDS operations in flight, oldest first: two piece writes, a0, b0, b1, b2, b3, a1
-    RF_WAIT2(a0, b0, 8)
+    // LDS operations in flight, oldest first: two piece writes, a0, b0, b1, b2, b3, (a1)
+    RF_WAIT2(a0, b0, 6 + kA1)
     RF_MFMA(0, 0, a0, b0)
     RF_FENCE
-    RF_WAIT1(b1, 6)
+    RF_WAIT1(b1, 4 + kA1)
     RF_MFMA(0, 1, a0, b1)
     RF_FENCE
-    RF_WAIT1(b2, 4)
+    RF_WAIT1(b2, 2 + kA1)
     RF_MFMA(0, 2, a0, b2)
     RF_FENCE
-    RF_WAIT1(b3, 2)
+    RF_WAIT1(b3, kA1)
     RF_MFMA(0, 3, a0, b3)
     RF_FENCE
-    RF_WAIT1(a1, 0)  // every read of ring slot slot1 is back
+    if constexpr (NI == 2) { RF_WAIT1(a1, 0) }  // every read of ring slot slot1 is back
     RF_QUANT_STORE(2, st ^ 1)
     RF_LOAD_X(2, min(s + 2, nk - 1))
     RF_QUANT_STORE(3, st ^ 1)
     RF_LOAD_X(3, min(s + 2, nk - 1))
-    RF_MFMA(1, 0, a1, b0)
+    if constexpr (NI == 2) { RF_MFMA(1, 0, a1, b0) }
     RF_ISSUE_W(min(2 * s + 4, nkk - 1), slot1)
     RF_FENCE
-    RF_MFMA(1, 1, a1, b1)
-    RF_MFMA(1, 2, a1, b2)
-    RF_MFMA(1, 3, a1, b3)
+    if constexpr (NI == 2) {
+      RF_MFMA(1, 1, a1, b1)
+      RF_MFMA(1, 2, a1, b2)
+      RF_MFMA(1, 3, a1, b3)
+    }
     RF_FENCE
 #undef RF_READ32
 #undef RF_READ_A
@@ -402,10 +421,10 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     const float f = s_mfinal[mloc] * (1.0f / kE4M3Max);
     if (m >= M) continue;
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
+    for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = n0 + 64 * wave + 32 * ni + 8 * r4 + 4 * hh;
+        const int n = n0 + L::kWaveN * wave + 32 * ni + 8 * r4 + 4 * hh;
         if (n < N) {
           u32x2 o2;
           o2[0] = pack_bf16(acc[ni][mi][4 * r4] * f, acc[ni][mi][4 * r4 + 1] * f);
@@ -420,15 +439,25 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
 hipError_t launch_fp8_quant_gemm(const void* a, const void* w, void* c, int M, int K, int N,
                                  int64_t lda, int64_t ldw, int64_t ldc, hipStream_t s) {
   const int n_mtiles = (M + kQM - 1) / kQM;
-  const int n_ntiles = (N + kQN - 1) / kQN;
+  // The 512-wide N tile does the most work per byte staged.  When the 256-wide tiling still
+  // fits the chip in one round of workgroups (one per compute unit), it is taken instead: it
+  // occupies up to twice as many compute units and wastes less of a ragged last tile.
+  const int64_t n_narrow = (int64_t)n_mtiles * ((N + 255) / 256);
+  const int ni = n_narrow <= 256 ? 1 : 2;
+  const int n_ntiles = (N + 256 * ni - 1) / (256 * ni);
   const int64_t grid = (int64_t)n_mtiles * n_ntiles;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
   // 32-bit lane offsets: inside a 128-token tile of a, inside all of w
   if ((int64_t)kQM * lda * 2 >= ((int64_t)1 << 32) || (int64_t)N * ldw >= ((int64_t)1 << 32))
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(fp8_quant_gemm_kernel, dim3((unsigned)grid), dim3(kQThreads), 0, s,
-                     (const bf16_t*)a, (const unsigned char*)w, (bf16_t*)c, M, K, N, lda, ldw, ldc,
-                     n_ntiles);
+  if (ni == 1)
+    hipLaunchKernelGGL(fp8_quant_gemm_kernel<1>, dim3((unsigned)grid), dim3(kQThreads), 0, s,
+                       (const bf16_t*)a, (const unsigned char*)w, (bf16_t*)c, M, K, N, lda, ldw, ldc,
+                       n_ntiles);
+  else
+    hipLaunchKernelGGL(fp8_quant_gemm_kernel<2>, dim3((unsigned)grid), dim3(kQThreads), 0, s,
+                       (const bf16_t*)a, (const unsigned char*)w, (bf16_t*)c, M, K, N, lda, ldw, ldc,
+                       n_ntiles);
   return hipGetLastError();
 }
 

@@ -439,7 +439,10 @@ def _fp8_tensor(w_bits):
 
 
 @pytest.mark.parametrize("M,K,N", [(128, 256, 512), (77, 128, 72), (300, 512, 264), (1, 128, 8), (256, 1024, 1032),
-                                   (130, 384, 520)])
+                                   (130, 384, 520),
+                                   # more than 256 tiles of 256 channels: the 512-channel tiling, with a ragged
+                                   # last tile in both directions
+                                   (1152, 256, 7424), (1100, 384, 7400)])
 def test_fp8_quant_gemm_shapes(rf, M, K, N):
     say(f"fp8_quant_gemm M{M} K{K} N{N}")
     a, w, w_bits = I.fp8_quant_gemm_inputs(I.SEED_BASE + 7, M, K, N)

@@ -84,11 +84,12 @@ def check_waits(verbose=True):
     cc = hipcc()
     for src in SOURCES:
         path = os.path.join(CSRC, src)
-        if not check_isa.uses_asm_loads(path):
+        counters = check_isa.hand_counted(path)
+        if not counters:
             continue
-        n, hazards = check_isa.check_source(path, cc, HIPCC_FLAGS)
+        n, hazards = check_isa.check_source(path, cc, HIPCC_FLAGS, counters)
         if verbose:
-            print(f"check_isa {src}: {n} kernels, {len(hazards)} hazards", flush=True)
+            print(f"check_isa {src} ({'+'.join(counters)}): {n} kernels, {len(hazards)} hazards", flush=True)
         if hazards:
             raise RuntimeError(f"{src}: registers touched while their loads are in flight:\n  "
                                + "\n  ".join(hazards[:20]))

@@ -10,9 +10,11 @@ case that has been seen).  Such a copy reads the register's old contents and the
 computes garbage with no error.
 
 This module compiles a source to gfx950 assembly (device code only) and walks each kernel
-with a model of the in-order vector-memory counter: every vector-memory instruction joins a
-queue, ``s_waitcnt vmcnt(N)`` retires all but the newest N, and an instruction that names a
-register that a queued load will still write is reported.  The walk follows the text from
+with a model of the two in-order counters: every vector-memory instruction joins one queue and
+every LDS instruction another, ``s_waitcnt vmcnt(N)`` / ``lgkmcnt(N)`` retire all but the newest
+N of their queue, and an instruction that names a register that a queued load will still write
+is reported.  Scalar loads share the LDS counter but return out of order, so a partial
+``lgkmcnt`` wait with a scalar load in flight is reported as well.  The walk follows the text from
 top to bottom and then takes each backward branch once more from its target with the queue
 it had at the branch, which covers the steady state of a software-pipelined loop.  Forward
 branches are taken as falling through; that is exact for the kernels checked here, whose
@@ -35,6 +37,7 @@ _VM_PREFIX = ("global_load", "global_store", "global_atomic", "buffer_load", "bu
 _REG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
 _LABEL = re.compile(r"^([.\w$]+):")
 _VMCNT = re.compile(r"vmcnt\((\d+)\)")
+_LGKMCNT = re.compile(r"lgkmcnt\((\d+)\)")
 _BRANCH = re.compile(r"^s_c?branch\w*\s+([.\w$]+)")
 
 
@@ -76,49 +79,82 @@ def _parse(asm_text):
     return {k: v for k, v in kernels.items() if any(e[1].startswith("s_endpgm") for e in v if e[0] == "ins")}
 
 
-def _step(ins, queue, where, report):
-    """Apply one instruction to the queue of in-flight vector-memory operations."""
+class Queues:
+    """In-flight operations of the two counters that the kernels wait on by hand: vector
+    memory (vmcnt) and LDS / scalar memory (lgkmcnt).  Entries are (registers, text, kind)."""
+
+    def __init__(self, vm=None, lgkm=None):
+        self.vm = list(vm or [])
+        self.lgkm = list(lgkm or [])
+
+    def copy(self):
+        return Queues(self.vm, self.lgkm)
+
+
+def _step(ins, q, where, report, counters=("vm", "lgkm")):
+    """Apply one instruction to the queues of in-flight operations; hazards are reported for
+    the named counters only."""
     mnem, _, ops = ins.partition(" ")
     if mnem == "s_waitcnt":
         m = _VMCNT.search(ops)
         if m:
             keep = int(m.group(1))
-            del queue[: max(0, len(queue) - keep)]
+            del q.vm[: max(0, len(q.vm) - keep)]
+        m = _LGKMCNT.search(ops)
+        if m:
+            keep = int(m.group(1))
+            if keep == 0:
+                q.lgkm.clear()
+            elif any(kind == "smem" for _, _, kind in q.lgkm):
+                # scalar loads return out of order: a partial wait proves nothing about LDS reads
+                if "lgkm" in counters:
+                    report.append(f"{where}: `{ins}` is a partial wait while a scalar load is in flight")
+            else:
+                del q.lgkm[: max(0, len(q.lgkm) - keep)]
         return
     named = _regs(ops)
-    for dest, issued in queue:
+    for dest, issued, _ in (q.vm if "vm" in counters else []) + (q.lgkm if "lgkm" in counters else []):
         hit = named & dest
         if hit:
             report.append(f"{where}: `{ins}` names v{min(hit)} while `{issued}` is in flight")
             break
+    if mnem.startswith("ds_"):
+        dest = set()
+        if any(t in mnem for t in ("read", "load", "permute", "swizzle", "rtn")):
+            dest = _regs(ops.split(",")[0])
+        q.lgkm.append((dest, ins, "lds"))
+        return
+    if mnem.startswith(("s_load", "s_buffer_load")):
+        q.lgkm.append((set(), ins, "smem"))
+        return
     if mnem.startswith(_VM_PREFIX):
         dest = set()
         if "_load" in mnem and not re.search(r"\blds\b", ops) and "_lds_" not in mnem:
             dest = _regs(ops.split(",")[0])
         elif "atomic" in mnem and re.search(r"\b(sc0|glc)\b", ops):
             dest = _regs(ops.split(",")[0])
-        queue.append((dest, ins))
+        q.vm.append((dest, ins, "vmem"))
 
 
-def check_kernel(name, entries):
+def check_kernel(name, entries, counters=("vm", "lgkm")):
     """Return the list of hazards found in one kernel."""
     report = []
     labels = {p: i for i, (k, p) in enumerate(entries) if k == "label"}
-    queue = []
+    queue = Queues()
     at_branch = []
     for i, (kind, p) in enumerate(entries):
         if kind != "ins":
             continue
         m = _BRANCH.match(p)
         if m and m.group(1) in labels and labels[m.group(1)] < i:
-            at_branch.append((labels[m.group(1)], i, list(queue)))
-        _step(p, queue, f"{name} +{i}", report)
+            at_branch.append((labels[m.group(1)], i, queue.copy()))
+        _step(p, queue, f"{name} +{i}", report, counters)
     for start, end, q in at_branch:
-        q = list(q)
+        q = q.copy()
         for i in range(start, end):
             kind, p = entries[i]
             if kind == "ins":
-                _step(p, q, f"{name} +{i} (second trip)", report)
+                _step(p, q, f"{name} +{i} (second trip)", report, counters)
     seen, out = set(), []
     for r in report:
         key = r.split(": ", 1)[1]
@@ -128,16 +164,19 @@ def check_kernel(name, entries):
     return out
 
 
-def check_text(asm_text):
+def check_text(asm_text, counters=("vm", "lgkm")):
     hazards = []
     kernels = _parse(asm_text)
     for name, entries in kernels.items():
-        hazards += check_kernel(name, entries)
+        hazards += check_kernel(name, entries, counters)
     return len(kernels), hazards
 
 
-def check_source(path, hipcc, flags):
-    """Compile one HIP source to device assembly and check every kernel in it."""
+def check_source(path, hipcc, flags, counters=None):
+    """Compile one HIP source to device assembly and check every kernel in it, for the counters
+    that the source waits on by hand (see hand_counted) unless told otherwise."""
+    if counters is None:
+        counters = hand_counted(path)
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "dev.s")
         cmd = [hipcc, *flags, "--cuda-device-only", "-S", path, "-o", out]
@@ -145,12 +184,22 @@ def check_source(path, hipcc, flags):
         if r.returncode != 0:
             raise RuntimeError(f"hipcc -S failed on {path}:\n{r.stdout}")
         with open(out) as f:
-            return check_text(f.read())
+            return check_text(f.read(), counters)
 
 
-def uses_asm_loads(path):
+def hand_counted(path):
+    """The counters that a source waits on by hand: "vm" if it loads registers from global
+    memory in inline assembly, "lgkm" if it reads LDS in inline assembly.  Loads that the
+    compiler issues get the compiler's own waits; the model, which follows the text rather
+    than the control flow, is not meant for them."""
     with open(path) as f:
-        return re.search(r'asm[^;]*"global_load_dwordx\d %0', f.read()) is not None
+        text = f.read()
+    out = []
+    if re.search(r'asm[^;]*"global_load_dwordx\d %0', text):
+        out.append("vm")
+    if re.search(r'asm[^;]*"ds_read\w* %0', text):
+        out.append("lgkm")
+    return tuple(out)
 
 
 if __name__ == "__main__":

@@ -64,9 +64,29 @@ def test_direct_to_lds_loads_and_stores_count_but_own_no_registers():
     assert hazards(body) == []
 
 
+def test_lds_reads_waited_by_count_and_scalar_loads_in_between():
+    body = ("\tds_read_b128 v[4:7], v1\n"
+            "\tds_read_b64_tr_b16 v[8:9], v1 offset:64\n"
+            "\ts_waitcnt lgkmcnt(1)\n"
+            "\tv_mov_b32_e32 v20, v5\n")
+    assert hazards(body) == []
+    assert len(hazards(body + "\tv_mov_b32_e32 v21, v9\n")) == 1
+    # a scalar load shares the counter and may return first: the partial wait proves nothing
+    mixed = body.replace("\ts_waitcnt", "\ts_load_dwordx2 s[4:5], s[0:1], 0x0\n\ts_waitcnt")
+    hz = hazards(mixed)
+    assert any("partial wait" in h for h in hz)
+    # the vector-memory queue is left alone by an LDS wait
+    both = "\tglobal_load_dwordx4 v[30:33], v1, s[2:3]\n" + body + "\tv_mov_b32_e32 v22, v30\n"
+    assert len(hazards(both)) == 1
+    n, only_lgkm = C.check_text(HEAD + both + TAIL, counters=("lgkm",))
+    assert only_lgkm == []
+
+
 def test_sources_with_hand_counted_loads_are_found_and_clean():
-    checked = [s for s in B.SOURCES if C.uses_asm_loads(os.path.join(B.CSRC, s))]
-    assert set(checked) == {"rmsnorm_gemm.hip", "fp8_quant_gemm.hip"}
+    checked = {s: C.hand_counted(os.path.join(B.CSRC, s)) for s in B.SOURCES}
+    checked = {s: c for s, c in checked.items() if c}
+    assert checked["rmsnorm_gemm.hip"] == ("vm", "lgkm") and checked["fp8_quant_gemm.hip"] == ("vm", "lgkm")
+    assert checked["attention_bf16.hip"] == ("lgkm",)
     try:
         cc = B.hipcc()
     except RuntimeError:

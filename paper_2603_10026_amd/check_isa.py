@@ -15,10 +15,11 @@ every LDS instruction another, ``s_waitcnt vmcnt(N)`` / ``lgkmcnt(N)`` retire al
 N of their queue, and an instruction that names a register that a queued load will still write
 is reported.  Scalar loads share the LDS counter but return out of order, so a partial
 ``lgkmcnt`` wait with a scalar load in flight is reported as well.  The walk follows the text from
-top to bottom and then takes each backward branch once more from its target with the queue
-it had at the branch, which covers the steady state of a software-pipelined loop.  Forward
-branches are taken as falling through; that is exact for the kernels checked here, whose
-loops hold no divergent control flow between a load and its wait.
+top to bottom: a forward branch hands its state to its target, text behind an unconditional
+branch is skipped until a label that has been handed a state, and where states meet the one
+with the most operations in flight goes on.  Each backward branch is then taken once more from
+its target with the queue it had at the branch, which covers the steady state of a
+software-pipelined loop.
 
 ``python -m paper_2603_10026_amd.check_isa file.hip [...]`` prints what it finds and exits
 non-zero on a hazard.
@@ -136,25 +137,52 @@ def _step(ins, q, where, report, counters=("vm", "lgkm")):
         q.vm.append((dest, ins, "vmem"))
 
 
+def _longest(states):
+    return max(states, key=lambda q: len(q.vm) + len(q.lgkm))
+
+
+def _walk(name, entries, labels, start, end, state, counters, report, tag, back_edges=None):
+    """Walk entries[start:end] in text order from `state`.  A forward branch hands a copy of the
+    state to its target; after an unconditional branch the text is unreachable until a label
+    that some branch has handed a state to.  Where several states meet, the one with the most
+    operations in flight goes on.  Backward branches are recorded (with the state at the
+    branch) in back_edges."""
+    handed = {}
+    for i in range(start, end):
+        kind, p = entries[i]
+        if kind == "label":
+            incoming = handed.pop(i, [])
+            if state is not None:
+                incoming.append(state)
+            state = _longest(incoming).copy() if incoming else None
+            continue
+        if state is None:
+            continue
+        m = _BRANCH.match(p)
+        if m and m.group(1) in labels:
+            target = labels[m.group(1)]
+            if target > i:
+                handed.setdefault(target, []).append(state.copy())
+            elif back_edges is not None:
+                back_edges.append((target, i, state.copy()))
+            if p.startswith("s_branch"):
+                state = None
+            continue
+        if p.startswith("s_endpgm"):
+            state = None
+            continue
+        _step(p, state, f"{name} +{i}{tag}", report, counters)
+
+
 def check_kernel(name, entries, counters=("vm", "lgkm")):
     """Return the list of hazards found in one kernel."""
     report = []
     labels = {p: i for i, (k, p) in enumerate(entries) if k == "label"}
-    queue = Queues()
-    at_branch = []
-    for i, (kind, p) in enumerate(entries):
-        if kind != "ins":
-            continue
-        m = _BRANCH.match(p)
-        if m and m.group(1) in labels and labels[m.group(1)] < i:
-            at_branch.append((labels[m.group(1)], i, queue.copy()))
-        _step(p, queue, f"{name} +{i}", report, counters)
-    for start, end, q in at_branch:
-        q = q.copy()
-        for i in range(start, end):
-            kind, p = entries[i]
-            if kind == "ins":
-                _step(p, q, f"{name} +{i} (second trip)", report, counters)
+    back_edges = []
+    _walk(name, entries, labels, 0, len(entries), Queues(), counters, report, "", back_edges)
+    for target, branch, q in back_edges:
+        # from the label itself, so that the walk adopts the state handed to it
+        _walk(name, entries, labels, target + 1, branch, q, counters, report, " (second trip)")
     seen, out = set(), []
     for r in report:
         key = r.split(": ", 1)[1]

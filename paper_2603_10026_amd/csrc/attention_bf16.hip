@@ -403,10 +403,21 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
   }
 
   // ---- epilogue: O = acc / l ----
+  // The accumulators hold a query row per lane, four output values at a time: written to
+  // memory from there, every store instruction would touch 32 rows with 16 bytes each.  The
+  // rows go through LDS instead (the K/V buffers, once every wavefront is done with the last
+  // tile; same slot swizzle as a K tile) and leave as whole 16-byte pieces, a full row per 16
+  // (or 8) lanes.  A wavefront stages and stores its own 32 rows, so no barrier is needed in
+  // between.
   l += __shfl_xor(l, 32, 64);
   const float inv = l > 0.f ? 1.0f / l : 0.f;
-  if (my_q < Lq) {
-    bf16_t* op = o + (int64_t)b * so.b + (int64_t)h * so.h + (int64_t)my_q * so.l;
+  __syncthreads();
+  {
+    unsigned char* stage = lds + (wave * 32) * ROWB;
+    // (opaque copies: the addresses below are the same in both passes of a paired launch, and
+    // the compiler would otherwise compute them all up front and carry them through the loop)
+    int i32e = i32, lanee = lane;
+    asm volatile("" : "+v"(i32e), "+v"(lanee));
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
@@ -415,8 +426,18 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
         u32x2 w;
         w[0] = pack_bf16(acc[t][4 * r4] * inv, acc[t][4 * r4 + 1] * inv);
         w[1] = pack_bf16(acc[t][4 * r4 + 2] * inv, acc[t][4 * r4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(op + 32 * t + 8 * r4 + 4 * hh) = w;
+        *reinterpret_cast<u32x2*>(stage + i32e * ROWB + (((4 * t + r4) ^ fK<D>(i32e)) << 4) +
+                                  8 * (lanee >> 5)) = w;
       }
+    bf16_t* ob = o + (int64_t)b * so.b + (int64_t)h * so.h;
+#pragma unroll
+    for (int i = 0; i < 32 / ROWS_PER_LD; ++i) {
+      const int row = i * ROWS_PER_LD + lanee / P;   // within the wavefront's 32 rows
+      const int slot = lanee % P;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(stage + row * ROWB + ((slot ^ fK<D>(row)) << 4));
+      const int qrow = q0 + wave * 32 + row;
+      if (qrow < Lq) *reinterpret_cast<u32x4*>(ob + (int64_t)qrow * so.l + 8 * slot) = w;
+    }
   }
   }  // pass
 }

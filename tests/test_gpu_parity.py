@@ -170,6 +170,10 @@ ATTN_CASES = [
     ("bf16", 1, 176, 8, 700, 700, 128, True),      # pairs of 128-query tiles (odd count of 256-query tiles)
     ("bf16", 1, 176, 8, 768, 768, 64, True),
     ("bf16", 1, 128, 16, 1024, 600, 128, True),    # Lk < Lq: the light tile of each pair sees no key
+    # more 256-query workgroups than compute units, with a ragged last query tile
+    ("bf16", 1, 160, 8, 500, 300, 128, False),
+    ("bf16", 2, 80, 80, 512, 129, 64, False),
+    ("bf16", 1, 136, 8, 1000, 1300, 128, True),    # paired causal tiles, more workgroups than compute units
 ]
 
 

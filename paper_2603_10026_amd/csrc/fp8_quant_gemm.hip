@@ -414,6 +414,44 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   __syncthreads();
 
   // epilogue: c = acc * m / MAX
+  // An accumulator lane holds one token, four channels at a time: stored from there, an
+  // instruction would touch 32 rows with 16 bytes each.  When the output allows 16-byte stores,
+  // a wavefront stages its 128-token x kWaveN-channel sub-tile in LDS (everything but the final
+  // maxima is free by now; 16-byte slots XOR-swizzled with the row) and stores whole row
+  // segments of 64 or 128 bytes.
+  const bool wide_ok = (reinterpret_cast<uintptr_t>(c) & 15) == 0 && (ldc & 7) == 0;
+  if (wide_ok) {
+    constexpr int RB = L::kWaveN * 2;   // bytes per staged row
+    constexpr int SL = RB / 16;         // 16-byte slots per row (4 or 8)
+    unsigned char* stage = lds + wave * (kQM * RB);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const int row = 32 * mi + i32;
+      const float f = s_mfinal[row] * (1.0f / kE4M3Max);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          u32x2 o2;
+          o2[0] = pack_bf16(acc[ni][mi][4 * r4] * f, acc[ni][mi][4 * r4 + 1] * f);
+          o2[1] = pack_bf16(acc[ni][mi][4 * r4 + 2] * f, acc[ni][mi][4 * r4 + 3] * f);
+          const int sw = (RB == 128) ? ((row >> 1) & 7) : ((row >> 2) & 3);
+          *reinterpret_cast<u32x2*>(stage + row * RB + (((4 * ni + r4) ^ sw) << 4) + 8 * hh) = o2;
+        }
+    }
+    constexpr int RPI = 64 / SL;  // rows per store instruction
+#pragma unroll
+    for (int i = 0; i < kQM / RPI; ++i) {
+      const int row = RPI * i + lane / SL;
+      const int slot = lane % SL;
+      const int sw = (RB == 128) ? ((row >> 1) & 7) : ((row >> 2) & 3);
+      const u32x4 o4 = *reinterpret_cast<const u32x4*>(stage + row * RB + ((slot ^ sw) << 4));
+      const int m = m0 + row;
+      const int n = n0 + L::kWaveN * wave + 8 * slot;
+      if (m < M && n < N) *reinterpret_cast<u32x4*>(c + (int64_t)m * ldc + n) = o4;  // N is a multiple of 8
+    }
+    return;
+  }
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
     const int mloc = 32 * mi + i32;

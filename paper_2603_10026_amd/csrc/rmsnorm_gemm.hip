@@ -363,6 +363,48 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
   __syncthreads();
 
   // epilogue: y = acc * H(ss)
+  // An accumulator lane holds one output row, four columns at a time: stored from there, an
+  // instruction would touch 32 rows with 16 bytes each.  When the output allows 16-byte stores,
+  // a wavefront stages its 128 x 64 sub-tile in LDS (all stages are free by now; rows of 128
+  // bytes, 16-byte slots XOR-swizzled with the row) and stores whole 128-byte row segments.
+  const bool wide_ok = (reinterpret_cast<uintptr_t>(y) & 15) == 0 && (ldy & 7) == 0;
+  if (wide_ok) {
+    unsigned char* stage = lds + 1024 + wave * (kBM * 128);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const int row = 32 * mi + i32;
+      const float rs = s_rstd[row];
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          u32x2 o2;
+          o2[0] = pack_bf16(acc[ni][mi][4 * r4] * rs, acc[ni][mi][4 * r4 + 1] * rs);
+          o2[1] = pack_bf16(acc[ni][mi][4 * r4 + 2] * rs, acc[ni][mi][4 * r4 + 3] * rs);
+          *reinterpret_cast<u32x2*>(stage + row * 128 + (((4 * ni + r4) ^ ((row >> 1) & 7)) << 4) + 8 * hh) = o2;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kBM / 8; ++i) {
+      const int row = 8 * i + (lane >> 3);
+      const int slot = lane & 7;
+      const u32x4 o4 = *reinterpret_cast<const u32x4*>(stage + row * 128 + ((slot ^ ((row >> 1) & 7)) << 4));
+      const int m = m0 + row;
+      const int n = n0 + 64 * wave + 8 * slot;
+      if (m < M) {
+        bf16_t* dst = y + (int64_t)m * ldy + n;
+        if (n + 8 <= N) {
+          *reinterpret_cast<u32x4*>(dst) = o4;
+        } else if (n + 4 <= N) {
+          u32x2 o2;
+          o2[0] = o4[0];
+          o2[1] = o4[1];
+          *reinterpret_cast<u32x2*>(dst) = o2;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
     const int mloc = 32 * mi + i32;

@@ -2,8 +2,9 @@
  * rf_diag.h - measurement aids and the fusion-level study, exported by the same library as
  * rf.h but not part of the cascaded-reduction path.  Nothing in rf.h depends on them; they
  * exist so that the benchmark can report measured ceilings (a plain copy, a read-only sweep,
- * an MFMA-only loop) next to the published peaks, scale hardware traffic counters, and
- * repeat the paper's fusion-level comparison of the safe-softmax cascade (Section 5.3).
+ * an MFMA-only loop) next to the published peaks, scale hardware traffic counters,
+ * repeat the paper's fusion-level comparison of the safe-softmax cascade (Section 5.3) and
+ * compare two tilings of the attention cascade.
  * Conventions (device pointers owned by the caller, asynchronous on `stream`, status codes)
  * are those of rf.h.
  */
@@ -35,6 +36,17 @@ extern "C" {
  */
 RF_API rf_status rf_diag_softmax_level(const rf_tensor* x, rf_tensor* y, int level, float* ml_buf,
                                        rf_stream stream);
+
+/*
+ * Tiling study of the fused attention cascade (Section 4.3 single-segment strategy, Appendix
+ * A.4): the same result as rf_cascade_attention with causal == 0, computed by a kernel that
+ * gives every wavefront 64 query rows and a SIMD to itself (the entry point in rf.h gives it
+ * 32 rows and shares the SIMD between two wavefronts).  Kept to measure the two tilings side
+ * by side.  q, k, v, o as for rf_cascade_attention, bf16 only, head dimension 128, at least
+ * 64 keys, row pitches of k and v below 2^24 elements; other shapes: RF_ERR_UNSUPPORTED.
+ */
+RF_API rf_status rf_diag_attention_wide(const rf_tensor* q, const rf_tensor* k, const rf_tensor* v,
+                                        rf_tensor* o, float scale, rf_stream stream);
 
 /*
  * Measurement aids, not part of the cascaded-reduction path.  They provide the two

@@ -39,6 +39,7 @@ ENTRY_POINTS = (
 # measurement aids and the fusion-level study, declared in include/rf_diag.h
 DIAG_ENTRY_POINTS = (
     "rf_diag_softmax_level",
+    "rf_diag_attention_wide",
     "rf_diag_copy",
     "rf_diag_read",
     "rf_diag_mfma",
@@ -105,6 +106,8 @@ def load_library():
     lib.rf_fp8_quant_gemm.restype = ctypes.c_int
     lib.rf_fp8_quant_gemm.argtypes = [P, P, P, ctypes.c_void_p]
     lib.rf_diag_softmax_level.restype = ctypes.c_int
+    lib.rf_diag_attention_wide.argtypes = [P, P, P, P, ctypes.c_float, ctypes.c_void_p]
+    lib.rf_diag_attention_wide.restype = ctypes.c_int
     lib.rf_diag_softmax_level.argtypes = [P, P, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.rf_diag_copy.restype = ctypes.c_int
     lib.rf_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
@@ -304,6 +307,17 @@ def rf_diag_softmax_level(x, y, level, ml_buf=None, stream=None):
     _check(lib.rf_diag_softmax_level(ctypes.byref(dx), ctypes.byref(dy), int(level), p, _stream(stream)),
            "rf_diag_softmax_level")
     return y
+
+
+def rf_diag_attention_wide(q, k, v, scale, o=None, stream=None):
+    """The attention cascade (no mask) with 64 query rows per wavefront; tiling study aid."""
+    lib = load_library()
+    if o is None:
+        o = torch.empty_like(q)
+    dq, dk, dv, do = tensor_desc(q), tensor_desc(k), tensor_desc(v), tensor_desc(o)
+    _check(lib.rf_diag_attention_wide(ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dv), ctypes.byref(do),
+                                      ctypes.c_float(scale), _stream(stream)), "rf_diag_attention_wide")
+    return o
 
 
 def rf_diag_copy(src, dst, stream=None):

@@ -22,6 +22,7 @@ SOURCES = [
     "fp8_quant_gemm.hip",
     "attention_f32.hip",
     "attention_bf16.hip",
+    "attention_bf16_wide.hip",
     "attention_splitk.hip",
     "merge_states.hip",
     "rmsnorm_gemm.hip",

@@ -325,6 +325,29 @@ rf_status rf_cascade_attention(const rf_tensor* q, const rf_tensor* k, const rf_
   return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
 }
 
+rf_status rf_diag_attention_wide(const rf_tensor* q, const rf_tensor* k, const rf_tensor* v,
+                                 rf_tensor* o, float scale, rf_stream stream) {
+  rf::AttnShape a{};
+  rf_status st;
+  if ((st = check_qkv(q, k, v, &a)) != RF_OK) return st;
+  if ((st = check_tensor(o, 4, 4)) != RF_OK) return st;
+  if (o->dtype != q->dtype) return RF_ERR_UNSUPPORTED;
+  if (!same_shape(o, q)) return RF_ERR_INVALID_ARG;
+  if (o->shape[3] > 1 && o->stride[3] != 1) return RF_ERR_UNSUPPORTED;
+  if (q->dtype != RF_BF16 || a.d != 128 || a.Lk < 64) return RF_ERR_UNSUPPORTED;
+  if (k->stride[2] >= (1 << 24) || v->stride[2] >= (1 << 24)) return RF_ERR_UNSUPPORTED;
+  if (numel(q) == 0) return RF_OK;
+  if (q->data == nullptr || o->data == nullptr || k->data == nullptr || v->data == nullptr)
+    return RF_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(o) || !aligned16(k) || !aligned16(v)) return RF_ERR_ALIGNMENT;
+  a.scale = scale;
+  a.causal = false;
+  const hipError_t e = rf::launch_attention_bf16_wide(q->data, k->data, v->data, o->data, strides4(q),
+                                                      strides4(k), strides4(v), strides4(o), a,
+                                                      (hipStream_t)stream);
+  return e == hipSuccess ? RF_OK : RF_ERR_LAUNCH;
+}
+
 rf_status rf_cascade_attention_splitk(const rf_tensor* q, const rf_tensor* k, const rf_tensor* v,
                                       int num_splits, rf_tensor* part_m, rf_tensor* part_l,
                                       rf_tensor* part_acc, float scale, int causal,

@@ -30,6 +30,11 @@ hipError_t launch_attention_f32(const float* q, const float* k, const float* v, 
 hipError_t launch_attention_bf16(const void* q, const void* k, const void* v, void* o,
                                  Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so,
                                  const AttnShape& a, hipStream_t s);
+// measured variant: 64 query rows per wavefront, one wavefront per SIMD; no mask, head
+// dimension 128, Lk >= 64, K/V row pitches below 2^24 (other shapes: hipErrorInvalidValue)
+hipError_t launch_attention_bf16_wide(const void* q, const void* k, const void* v, void* o,
+                                 Strides4 sq, Strides4 sk, Strides4 sv, Strides4 so,
+                                 const AttnShape& a, hipStream_t s);
 
 // Partial states are contiguous: part_m, part_l [B,Hq,Lq,S]; part_acc [B,Hq,Lq,S,d].
 hipError_t launch_attention_splitk_bf16(const void* q, const void* k, const void* v,

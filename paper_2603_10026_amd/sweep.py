@@ -14,7 +14,12 @@ the further cascades (MoE routing R1-R8, FP8 quant + GEMM Q1-Q10, variance V1-V8
 each: the time of one call through the Python binding, and the time per call when 24 calls are
 captured in a HIP graph and replayed (the host side of a launch is then out of the number).
 
-    python -m paper_2603_10026_amd.sweep [--what splits|fusion|tables] [--splits 8,16,...] [--iters 20]
+``--what tilings``: the unmasked prefill cascade (head dimension 128) with 32 query rows per
+wavefront and two wavefronts per SIMD (rf_cascade_attention) against 64 rows per wavefront and
+one wavefront per SIMD (rf_diag_attention_wide), for several key lengths; the per-key-tile slope
+and the fixed cost of a launch follow from the lines.
+
+    python -m paper_2603_10026_amd.sweep [--what splits|fusion|tables|tilings] [--splits 8,16,...] [--iters 20]
 """
 import argparse
 import json
@@ -25,12 +30,14 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--splits", type=str, default="8,16,32,64,128,256,512")
     ap.add_argument("--iters", type=int, default=20)
-    ap.add_argument("--what", type=str, default="splits", choices=["splits", "fusion", "tables"])
+    ap.add_argument("--what", type=str, default="splits", choices=["splits", "fusion", "tables", "tilings"])
     args = ap.parse_args()
     if args.what == "fusion":
         return fusion_sweep(args.iters)
     if args.what == "tables":
         return tables_sweep(args.iters)
+    if args.what == "tilings":
+        return tilings_sweep(args.iters)
     import torch
     from . import binding as rf
     from . import inputs as I
@@ -74,6 +81,39 @@ def main():
         del parts, outs
     best = min(rows, key=lambda r: r["us_median"])
     print(json.dumps(dict(best_num_splits=best["num_splits"], us_median=best["us_median"])), flush=True)
+
+
+def tilings_sweep(iters):
+    import torch
+    from . import binding as rf
+    from . import inputs as I
+
+    rf.load_library()
+    dev = "cuda:0"
+    c = I.WORKLOADS[2]
+    scale = I.default_scale(c["d"])
+    for Lk in (512, 1024, 2048, 4096, 8192):
+        q, k, v = I.attention_inputs_device(I.SEED_BASE + 2, c["B"], c["Hq"], c["Hkv"], c["Lq"], Lk, c["d"], "bf16", dev)
+        o = torch.empty_like(q)
+        flops = 4.0 * c["B"] * c["Hq"] * c["Lq"] * Lk * c["d"]
+        row = dict(workload=f"attn_prefill_bf16_B{c['B']}_H{c['Hq']}_Lq{c['Lq']}_Lk{Lk}_d{c['d']}_noncausal")
+        for name, fn in (("rows32_two_wavefronts_per_simd", lambda: rf.rf_cascade_attention(q, k, v, scale, causal=False, o=o)),
+                         ("rows64_one_wavefront_per_simd", lambda: rf.rf_diag_attention_wide(q, k, v, scale, o=o))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+            for i in range(iters):
+                evs[i][0].record()
+                fn()
+                evs[i][1].record()
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            med = ts[len(ts) // 2]
+            row[name] = dict(us_median=round(med, 1), TFLOPs=round(flops / med / 1e6, 1))
+        print(json.dumps(row), flush=True)
+        del q, k, v, o
+    return 0
 
 
 def fusion_sweep(iters):

@@ -213,6 +213,46 @@ def test_attention_empty_keys(rf):
     assert float(o.abs().max()) == 0.0
 
 
+WIDE_CASES = [
+    # B, Hq, Hkv, Lq, Lk: head dimension 128, no mask, at least 64 keys
+    (1, 2, 2, 256, 256),
+    (1, 1, 1, 64, 64),          # a single key tile
+    (2, 4, 2, 300, 450),        # ragged query tile, ragged last key tile (moved back to end at the last key)
+    (1, 8, 8, 384, 320),        # 5 key tiles: three surplus iterations on all-masked tiles
+    (1, 2, 1, 512, 1000),
+    (1, 3, 3, 1, 65),           # one query row; the second key tile holds one new key
+    (1, 160, 8, 500, 300),      # more workgroups than compute units
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Lq,Lk", WIDE_CASES)
+def test_attention_wide_variant(rf, B, Hq, Hkv, Lq, Lk):
+    say(f"attention, 64 rows per wavefront: B{B} Hq{Hq} Hkv{Hkv} Lq{Lq} Lk{Lk}")
+    q, k, v = I.attention_inputs(I.SEED_BASE + 5, B, Hq, Hkv, Lq, Lk, 128, "bf16")
+    scale = I.default_scale(128)
+    tq, tk, tv = (I.to_torch(a, "bf16", DEV) for a in (q, k, v))
+    o = torch.full_like(tq, float("nan"))
+    rf.rf_diag_attention_wide(tq, tk, tv, scale, o=o)
+    torch.cuda.synchronize()
+    check(o, O.attention(q, k, v, scale, False), "bf16", "attention wide")
+
+
+def test_attention_wide_variant_scales_and_refusals(rf):
+    say("attention, 64 rows per wavefront: negative and zero scale, large logits; unsupported shapes")
+    q, k, v = I.attention_inputs(78, 1, 2, 2, 200, 333, 128, "bf16")
+    q[0, 0, 3] *= 30.0
+    tq, tk, tv = (I.to_torch(a, "bf16", DEV) for a in (q, k, v))
+    for scale in (-I.default_scale(128), 0.0):
+        o = rf.rf_diag_attention_wide(tq, tk, tv, scale)
+        torch.cuda.synchronize()
+        check(o, O.attention(q, k, v, scale, False), "bf16", f"attention wide scale={scale}")
+    with pytest.raises(rf.RfError):          # fewer than 64 keys
+        rf.rf_diag_attention_wide(tq, tk[:, :, :63], tv[:, :, :63], 1.0)
+    q64 = torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(rf.RfError):          # head dimension 64
+        rf.rf_diag_attention_wide(q64, q64, q64, 1.0)
+
+
 # ------------------------------------------------------------ split + merge
 SPLIT_CASES = [
     # B, Hq, Hkv, Lq, Lk, S, causal

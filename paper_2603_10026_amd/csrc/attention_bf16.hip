@@ -367,7 +367,7 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
     }
     // ---- stage 2: running sum of exponentials; P^T packed to bf16 B operands ----
     const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-    float psum = 0.f;
+    float psum = 0.f, psum1 = 0.f;
     u32x4 pb[4];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
@@ -375,10 +375,16 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
       for (int r2 = 0; r2 < 8; ++r2) {
         const float p0 = fast_exp2(fmaf(s[rt][2 * r2], scale_log2e, neg_m));
         const float p1 = fast_exp2(fmaf(s[rt][2 * r2 + 1], scale_log2e, neg_m));
-        psum += p0 + p1;
-        pb[2 * rt + (r2 >> 2)][r2 & 3] = pack_bf16(p0, p1);
+        const uint32_t pk = pack_bf16(p0, p1);
+        pb[2 * rt + (r2 >> 2)][r2 & 3] = pk;
+        // one dot instruction adds the pair; the sum runs over the rounded probabilities,
+        // the values the second product sees (two chains: the additions do not wait on each other)
+        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+        if (rt == 0) psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum, false);
+        else psum1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, psum1, false);
       }
-    l += psum;
+    l += psum + psum1;
     // ---- stage 3: acc += V^T P^T ----
     constexpr int NV = 2 * DT;  // transpose reads per contraction step
     RF_WAIT_V(0, NV)

@@ -180,6 +180,14 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
     }
   };
 
+  // The first K/V tile of the workgroup's first query tile is requested here, before the rest of
+  // the set-up (LDS read offsets, Q fragments, masks): the trip to memory then overlaps it.
+  {
+    const int last_row0 = min(Lq - 1, qt * kBQ + kBQ - 1);
+    const int wg_last0 = causal ? min(Lk - 1, last_row0 + (Lk - Lq)) : Lk - 1;
+    if (wg_last0 >= 0) issue_loads(0, 0);
+  }
+
   // ---- LDS read offsets (loop invariant) ----
   int koff[KS];  // + rt * 32 * ROWB
 #pragma unroll
@@ -402,7 +410,7 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
 #undef RF_PV_STEP
   };
 
-  if (n_ktiles > 0) issue_loads(0, 0);
+  if (pass && n_ktiles > 0) issue_loads(0, 0);   // (first pass: requested during the set-up)
   for (int kt = 0; kt < n_ktiles; kt += 2) {
     tile_step(kt, std::integral_constant<int, 0>{});
     if (kt + 1 < n_ktiles) tile_step(kt + 1, std::integral_constant<int, 1>{});

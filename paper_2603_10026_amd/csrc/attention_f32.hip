@@ -77,21 +77,40 @@ __global__ __launch_bounds__(NW * kWave) void attention_f32_kernel(
   // requested before the first product, so memory latency is paid once per group, not twice
   // per tile (at the small sizes this kernel serves, that latency is most of the run time).
   constexpr int TG = (D == 64 && NW <= 8) ? 4 : 2;
+  const bool small_pitch = sk.l < (1 << 26) && sv.l < (1 << 26);  // 32-bit byte offsets inside a 16-key tile
+  const uint32_t k_lane = (uint32_t)(((int64_t)i16 * sk.l + 4 * g) * 4);
+  const uint32_t v_lane = (uint32_t)(((int64_t)(4 * g) * sv.l + DJ * i16) * 4);
   for (int kt0 = wave; kt0 < n_ktiles; kt0 += NW * TG) {
     f32x4 kf[TG][DJ];
     f32x4 vf[TG][4][DJ / 4];  // vf[.][u][c][e] = V[key of step u][DJ * i16 + 4c + e]
 #pragma unroll
     for (int jj = 0; jj < TG; ++jj) {
       const int key0 = min(kt0 + NW * jj, n_ktiles - 1) * 16;  // (a surplus slot re-reads the last tile)
-      const float* kp = kb + (int64_t)min(key0 + i16, Lk - 1) * sk.l + 4 * g;
+      if (key0 + 16 <= Lk && small_pitch) {
+        // whole tile: a wavefront-uniform base (scalar unit) plus loop-invariant 32-bit lane
+        // offsets, no per-lane 64-bit address arithmetic (which is most of this kernel's set-up)
+        const char* kbase = reinterpret_cast<const char*>(kb) + (int64_t)key0 * sk.l * 4;
 #pragma unroll
-      for (int j = 0; j < DJ; ++j) kf[jj][j] = *reinterpret_cast<const f32x4*>(kp + 16 * j);
+        for (int j = 0; j < DJ; ++j)
+          kf[jj][j] = *reinterpret_cast<const f32x4*>(kbase + k_lane + 64 * j);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        // contraction slot g of step u stands for key key0 + 4g + u
-        const float* vp = vb + (int64_t)min(key0 + 4 * g + u, Lk - 1) * sv.l + DJ * i16;
+        for (int u = 0; u < 4; ++u) {
+          // contraction slot g of step u stands for key key0 + 4g + u
+          const char* vbase = reinterpret_cast<const char*>(vb) + (int64_t)(key0 + u) * sv.l * 4;
 #pragma unroll
-        for (int c = 0; c < DJ / 4; ++c) vf[jj][u][c] = *reinterpret_cast<const f32x4*>(vp + 4 * c);
+          for (int c = 0; c < DJ / 4; ++c)
+            vf[jj][u][c] = *reinterpret_cast<const f32x4*>(vbase + v_lane + 16 * c);
+        }
+      } else {
+        const float* kp = kb + (int64_t)min(key0 + i16, Lk - 1) * sk.l + 4 * g;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) kf[jj][j] = *reinterpret_cast<const f32x4*>(kp + 16 * j);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float* vp = vb + (int64_t)min(key0 + 4 * g + u, Lk - 1) * sv.l + DJ * i16;
+#pragma unroll
+          for (int c = 0; c < DJ / 4; ++c) vf[jj][u][c] = *reinterpret_cast<const f32x4*>(vp + 4 * c);
+        }
       }
     }
 #pragma unroll

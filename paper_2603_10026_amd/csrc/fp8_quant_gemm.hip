@@ -16,11 +16,16 @@
 //   A operand = W rows: every wavefront streams ITS OWN 64 (or 32) output channels HBM -> LDS with
 //               direct-to-LDS 128-bit loads into a private ring of three 64-k slots; no
 //               other wavefront reads them, so no barrier guards them.
-//   B operand = quantised tokens: a tile of `a` is loaded into registers one step ahead,
-//               its maximum is merged into the running maximum (4 lanes share a token),
-//               it is scaled, rounded to FP8 with v_cvt_pk_fp8_f32 and written to LDS
-//               (two stages); the rescale factor m_old / m_new travels with the stage.
-// The vector-ALU work of the quantisation is cut into pieces placed between the MFMAs.
+//   B operand = quantised tokens: a tile of `a` is loaded into registers, its maximum is
+//               merged into the running maximum (4 lanes share a token), it is scaled,
+//               rounded to FP8 with v_cvt_pk_fp8_f32 and written to LDS two steps before it
+//               is multiplied (three stages); the rescale factor m_old / m_new travels with
+//               the stage.
+// With three token stages the one barrier of a step does not have to sit in front of the
+// step's first LDS reads: it sits behind the first four MFMAs, and the fragments of a step's
+// first weight tile are requested at the end of the step before, so no wavefront waits for
+// LDS data right behind a barrier.
+// The vector-ALU work of the quantisation is cut into half pieces placed behind the MFMAs.
 // All waits are hand-placed; loads retire in order, which fixes the counts.
 #include "rf_device.h"
 #include "rf_launch.h"
@@ -33,6 +38,7 @@ constexpr int kQWaves = 8;
 constexpr int kQThreads = kQWaves * kWave;
 constexpr int kQM = 128, kQK = 128;              // K step in elements = bytes of FP8
 constexpr int kQXStageB = kQM * kQK;             // 16 KB: [m][k] bytes, 128-byte rows
+constexpr int kQXStages = 3;                     // token tiles s, s+1 (being read) and s+2 (being written)
 // A wavefront owns NI blocks of 32 output channels: the N tile of a workgroup is 256 NI wide.
 template <int NI>
 struct QLayout {
@@ -43,8 +49,8 @@ struct QLayout {
   static constexpr int kWLoads = 2 * NI;              // direct-to-LDS loads per 64-k weight tile
   static constexpr int kWBase = 0;
   static constexpr int kXBase = kQWaves * kWRingB;    // 48 or 96 KB
-  static constexpr int kCorrBase = kXBase + 2 * kQXStageB;
-  static constexpr int kLdsB = kCorrBase + 2 * kQM * 4 + kQM * 4;  // + 2 stages of factors + final maxima
+  static constexpr int kCorrBase = kXBase + kQXStages * kQXStageB;
+  static constexpr int kLdsB = kCorrBase + kQXStages * kQM * 4 + kQM * 4;  // + factors per stage + final maxima
 };
 constexpr float kE4M3Max = 448.0f;
 
@@ -109,15 +115,14 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
   const int xq = tid & 3;
   const char* abase = reinterpret_cast<const char*>(a + (int64_t)m0 * lda);  // + step * 256 bytes
   const uint32_t alane_off = (uint32_t)(((int64_t)min(xrow, M - 1 - m0) * lda + 8 * xq) * 2);
-  uint32_t xdst_addr[2][4];  // [stage][piece]: LDS byte address of the piece's 8 FP8 codes
-#pragma unroll
-  for (int p4 = 0; p4 < 4; ++p4) {
-    xdst_addr[0][p4] = lds_base + kQXBase + xrow * 128 +
-                       (((2 * p4 + (xq >> 1)) ^ fQX(xrow)) << 4) + 8 * (xq & 1);
-    xdst_addr[1][p4] = xdst_addr[0][p4] + kQXStageB;
-  }
-  float* s_corr = reinterpret_cast<float*>(lds + kQCorrBase);          // [2][128]
-  float* s_mfinal = reinterpret_cast<float*>(lds + kQCorrBase) + 2 * kQM;  // [128]
+  // LDS byte address of piece 0's 8 FP8 codes in stage 0.  Piece p sits in slot (2 p + (xq >> 1)) ^ fQX of
+  // the 128-byte row, so its address differs from piece 0's in bits 5 and 6 only: XOR with 32 p.
+  const uint32_t xdst_addr0 = lds_base + kQXBase + xrow * 128 + (((xq >> 1) ^ fQX(xrow)) << 4) + 8 * (xq & 1);
+  // Rescale factors: [stage][token % 32][token / 32], so that an accumulator lane (one token of each
+  // of the four 32-token blocks) fetches its four factors with one 128-bit read.
+  const uint32_t corr_waddr = lds_base + kQCorrBase + ((xrow & 31) * 4 + (xrow >> 5)) * 4;
+  const uint32_t corr_raddr = lds_base + kQCorrBase + i32 * 16;
+  float* s_mfinal = reinterpret_cast<float*>(lds + kQCorrBase) + kQXStages * kQM;  // [128]
 
   // ---- weight role: 2 NI direct-to-LDS loads per wavefront per 64-k tile, 16 channels each ----
   uint32_t wsrc_off[kWL];  // byte offset from w + (64-k tile) * 64
@@ -152,14 +157,9 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     for (int h2 = 0; h2 < 2; ++h2)
       xaddr[kk][h2] = lds_base + kQXBase + i32 * 128 + (((4 * kk + 2 * hh + h2) ^ fQX(i32)) << 4);
   // A operand (weights): row 32 ni + i32 of the slot, slots 2 hh + {0, 1}
-  uint32_t waddr[NI][2];  // [ni][half] in slot 0
+  uint32_t waddr[2];  // [half] in slot 0; + ni * 32 * 64, + slot
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-    for (int h2 = 0; h2 < 2; ++h2) {
-      const int row = 32 * ni + i32;
-      waddr[ni][h2] = wring + row * 64 + (((2 * hh + h2) ^ fQW(row)) << 4);
-    }
+  for (int h2 = 0; h2 < 2; ++h2) waddr[h2] = wring + i32 * 64 + (((2 * hh + h2) ^ fQW(i32)) << 4);
 
   f32x16 acc[NI][4];  // [ni][mi]: C^T tile (rows = channels, columns = tokens)
 #pragma unroll
@@ -171,16 +171,16 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
 
   // ---- token tile in registers: 4 x 8 bf16 ----
   u32x4 xreg[4];
-#define RF_LOAD_X(P, STEP)                                                                    \
+#define RF_LOAD_X(REG, P, STEP)                                                               \
   {                                                                                           \
     const char* ap_ = abase + (int64_t)(STEP) * (kQK * 2);                                    \
     asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"                                   \
-                 : "=v"(xreg[P]) : "v"(alane_off), "s"(ap_), "n"(64 * (P)));                  \
+                 : "=v"(REG[P]) : "v"(alane_off), "s"(ap_), "n"(64 * (P)));                   \
   }
-#define RF_WAIT_X2(P0, P1, PENDING) \
-  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(xreg[P0]), "+v"(xreg[P1]) : "n"(PENDING));
-  // running state of this thread's token (the 4 lanes of a token hold the same values)
-  float m_run = 0.f, m_done = 0.f;
+#define RF_WAIT_X2(REG, P0, P1, PENDING) \
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(REG[P0]), "+v"(REG[P1]) : "n"(PENDING));
+  // running maximum of this thread's token (the 4 lanes of a token hold the same values)
+  float m_run = 0.f;
   float amax = 0.f, qscale = 0.f;
   unsigned amax_bits = 0;  // packed pair of running 16-bit maxima of the tile
   // max |x| of 8 bf16 values.  For non-negative values the bf16 bit patterns order like
@@ -198,219 +198,270 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
     const unsigned short m16 = v[0] > v[1] ? v[0] : v[1];
     return __uint_as_float((uint32_t)m16 << 16);
   };
-  // piece P: 8 values -> 8 FP8 codes -> LDS (raw write: the compiler would order an ordinary
-  // one behind the direct-to-LDS loads in flight)
-#define RF_QUANT_STORE(P, STAGE)                                                              \
+  // piece P: 8 values -> 8 FP8 codes -> LDS; XW = address of piece 0 in the stage (raw write: the compiler
+  // would order an ordinary one behind the direct-to-LDS loads in flight)
+#define RF_QUANT_A(REG, P, T0)                                                                \
   {                                                                                           \
-    int t0_ = 0, t1_ = 0;                                                                     \
-    t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][0]) * qscale, bf16_hi(xreg[P][0]) * qscale, t0_, false); \
-    t0_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][1]) * qscale, bf16_hi(xreg[P][1]) * qscale, t0_, true);  \
-    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][2]) * qscale, bf16_hi(xreg[P][2]) * qscale, t1_, false); \
-    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(xreg[P][3]) * qscale, bf16_hi(xreg[P][3]) * qscale, t1_, true);  \
+    T0 = 0;                                                                                   \
+    T0 = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(REG[P][0]) * qscale, bf16_hi(REG[P][0]) * qscale, T0, false); \
+    T0 = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(REG[P][1]) * qscale, bf16_hi(REG[P][1]) * qscale, T0, true);  \
+  }
+#define RF_QUANT_B(REG, P, T0, XW)                                                            \
+  {                                                                                           \
+    int t1_ = 0;                                                                              \
+    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(REG[P][2]) * qscale, bf16_hi(REG[P][2]) * qscale, t1_, false); \
+    t1_ = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(REG[P][3]) * qscale, bf16_hi(REG[P][3]) * qscale, t1_, true);  \
     u32x2 q2_;                                                                                \
-    q2_[0] = (uint32_t)t0_;                                                                   \
+    q2_[0] = (uint32_t)(T0);                                                                  \
     q2_[1] = (uint32_t)t1_;                                                                   \
-    asm volatile("ds_write_b64 %0, %1" : : "v"(xdst_addr[STAGE][P]), "v"(q2_) : "memory");    \
+    asm volatile("ds_write_b64 %0, %1" : : "v"((XW) ^ (32u * (P))), "v"(q2_) : "memory");     \
+  }
+#define RF_QUANT_STORE(REG, P, XW) \
+  {                                \
+    int t0_;                       \
+    RF_QUANT_A(REG, P, t0_)        \
+    RF_QUANT_B(REG, P, t0_, XW)    \
   }
   // merge the tile maximum into the running maximum; scale and rescale factor of the tile
-  auto update_max = [&](int stage_next) {
+  // (one LDS write per step, issued by every lane so that the wait counts below hold as written)
+  auto update_max = [&](int stage) {
     amax = fmaxf(amax, dpp_f32<kDppQuadXor1>(amax));
     amax = fmaxf(amax, dpp_f32<kDppQuadXor2>(amax));
     const float m_new = fmaxf(m_run, amax);
     qscale = m_new > 0.f ? kE4M3Max / m_new : 0.f;  // IEEE division: it decides the FP8 codes
     const float corr = (m_new == m_run) ? 1.0f : m_run * fast_rcp(m_new);
     m_run = m_new;
-    if (xq == 0) s_corr[stage_next * kQM + xrow] = corr;
+    const uint32_t ca = corr_waddr + stage * (kQM * 4);
+    asm volatile("ds_write_b32 %0, %1" : : "v"(ca), "v"(corr) : "memory");  // same value from the 4 lanes of a token
+  };
+
+  // Fragment registers: one 32-byte operand = two 128-bit halves.  They are carried from step to
+  // step: the fragments of the first weight tile of step s+1 are requested at the end of step s,
+  // into registers as those fall dead (an operand is dead once the last MFMA that reads it has
+  // been issued; LDS data comes back long after that MFMA has read its sources).
+  i32x8 a0, a1, b0, b1, b2, b3;
+  f32x4 corrv;  // rescale factors of the coming step for this lane's four tokens
+  // (the two halves are joined where they are requested, so that the operand is one value from
+  // there on: the compiler then only has whole operands to carry around the loop)
+#define RF_READ32(DST, ADDR0, ADDR1, OFF)                                                     \
+  {                                                                                           \
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_;                     \
+    i32x4_ lo_, hi_;                                                                          \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(lo_) : "v"(ADDR0), "n"(OFF));         \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(hi_) : "v"(ADDR1), "n"(OFF));         \
+    DST = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);                          \
+  }
+  // wait until at most PENDING LDS operations are in flight; the named operand is tied
+  // to the wait so that its uses stay behind it
+#define RF_WAIT2(X, Y, PENDING) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(X), "+v"(Y) : "n"(PENDING));
+#define RF_WAIT1(X, PENDING) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(X) : "n"(PENDING));
+#define RF_MFMA(NI_, MI, A, B)                                                                \
+  acc[NI_][MI] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, acc[NI_][MI], 0, 0, 0, 0x7f7f7f7f, 0, \
+                                                                 0x7f7f7f7f);
+#define RF_FENCE __builtin_amdgcn_sched_barrier(0);
+  auto any_rescale = [&]() {
+    return __builtin_amdgcn_ballot_w64(corrv[0] != 1.0f || corrv[1] != 1.0f || corrv[2] != 1.0f ||
+                                       corrv[3] != 1.0f) != 0;
   };
 
   // ---- prologue ----
-  // weight tile 0, token tile 0 (quantised into stage 0), then token tile 1 and weight
-  // tiles 1, 2 in the issue order of a loop step
+  // Token tiles 0 and 1 are quantised into stages 0 and 1, tile 2 is requested into registers,
+  // weight tiles 0, 1, 2 into the ring; vector-memory requests in the order of a loop step.
   RF_ISSUE_W(0, 0)
-  RF_LOAD_X(0, 0) RF_LOAD_X(1, 0) RF_LOAD_X(2, 0) RF_LOAD_X(3, 0)
-  RF_WAIT_X2(0, 1, 0) RF_WAIT_X2(2, 3, 0)
-  amax = fold_max(__builtin_elementwise_max(__builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])),
-                                            __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
-  update_max(0);
-  RF_QUANT_STORE(0, 0) RF_QUANT_STORE(1, 0) RF_QUANT_STORE(2, 0) RF_QUANT_STORE(3, 0)
   {
+    u32x4 xpro[4];  // token tile 1
     const int s1 = min(1, nk - 1);
-    RF_LOAD_X(0, s1) RF_LOAD_X(1, s1)
+    RF_LOAD_X(xreg, 0, 0) RF_LOAD_X(xreg, 1, 0) RF_LOAD_X(xreg, 2, 0) RF_LOAD_X(xreg, 3, 0)
+    RF_LOAD_X(xpro, 0, s1) RF_LOAD_X(xpro, 1, s1) RF_LOAD_X(xpro, 2, s1) RF_LOAD_X(xpro, 3, s1)
+    RF_WAIT_X2(xreg, 0, 1, 4) RF_WAIT_X2(xreg, 2, 3, 4)
+    amax = fold_max(__builtin_elementwise_max(__builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])),
+                                              __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
+    update_max(0);
+    RF_QUANT_STORE(xreg, 0, xdst_addr0) RF_QUANT_STORE(xreg, 1, xdst_addr0)
+    RF_QUANT_STORE(xreg, 2, xdst_addr0) RF_QUANT_STORE(xreg, 3, xdst_addr0)
+    RF_WAIT_X2(xpro, 0, 1, 0) RF_WAIT_X2(xpro, 2, 3, 0)  // (weight tile 0, the oldest request, has landed too)
+    amax = fold_max(__builtin_elementwise_max(__builtin_elementwise_max(absmax8(xpro[0]), absmax8(xpro[1])),
+                                              __builtin_elementwise_max(absmax8(xpro[2]), absmax8(xpro[3]))));
+    update_max(1);
+    RF_QUANT_STORE(xpro, 0, xdst_addr0 + kQXStageB) RF_QUANT_STORE(xpro, 1, xdst_addr0 + kQXStageB)
+    RF_QUANT_STORE(xpro, 2, xdst_addr0 + kQXStageB) RF_QUANT_STORE(xpro, 3, xdst_addr0 + kQXStageB)
+    const int s2 = min(2, nk - 1);
+    RF_LOAD_X(xreg, 0, s2)
     RF_ISSUE_W(min(1, nkk - 1), 1)
-    RF_LOAD_X(2, s1) RF_LOAD_X(3, s1)
+    RF_LOAD_X(xreg, 1, s2) RF_LOAD_X(xreg, 2, s2) RF_LOAD_X(xreg, 3, s2)
     RF_ISSUE_W(min(2, nkk - 1), 2)
   }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();  // token stages 0 and 1 and their factors are complete
+  asm volatile("ds_read_b128 %0, %1" : "=v"(corrv) : "v"(corr_raddr));
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(corrv));
+  bool resc = any_rescale();
+  RF_READ32(a0, waddr[0], waddr[1], 0)
+  RF_READ32(b0, xaddr[0][0], xaddr[0][1], 0 * 4096)
+  RF_READ32(b1, xaddr[0][0], xaddr[0][1], 1 * 4096)
+  RF_READ32(b2, xaddr[0][0], xaddr[0][1], 2 * 4096)
+  RF_READ32(b3, xaddr[0][0], xaddr[0][1], 3 * 4096)
+  if constexpr (NI == 2) { RF_READ32(a1, waddr[0], waddr[1], 32 * 64) }
 
   // ---- main loop ----
-  // Step s multiplies token stage s%2 by weight tiles 2s, 2s+1 (ring slots wslot,
-  // wslot+1), quantises token tile s+1 into stage (s+1)%2, fetches token tile s+2 into
-  // registers and weight tiles 2s+3, 2s+4 into the slots just read.  Every step is the same
-  // straight-line code: past the end of K the prefetches re-read the last tile (nothing
-  // consumes it) and the running maximum is taken from a snapshot made before the surplus
-  // quantisation.  Vector-memory issue order per step: X0, X1, W(2s+3), X2, X3, W(2s+4), where a
-  // weight tile is kWL loads.
-  int wslot = 0;
+  // Step s multiplies token stage s%3 by weight tiles 2s, 2s+1 (ring slots wslot, wslot+1),
+  // quantises token tile s+2 into stage (s+2)%3, fetches token tile s+3 into registers and weight
+  // tiles 2s+3, 2s+4 into the slots just read, and requests the fragments of weight tile 2s+2
+  // and token stage (s+1)%3 for the next step.  The one barrier of a step sits after its first
+  // four MFMAs: it orders the token writes of step s-1 (all finished before a wavefront arrives)
+  // before their reads (which start at the end of step s), and the reads of step s-1 before the
+  // writes of step s into the same stage (which follow the barrier), so no wavefront waits for
+  // LDS data right behind a barrier.  Every step is the same straight-line code: past the end
+  // of K the prefetches re-read the last tile, which leaves the maxima as they are, and nothing
+  // consumes them.  Vector-memory issue order per step: X0, W(2s+3), X1, X2, X3, W(2s+4), where a
+  // weight tile is kWL loads.  LDS operations in flight at the top of a step, oldest first: up to
+  // three piece writes of the previous step, a0, b0, b1, b2, b3, (a1).
+  int wslot = 0;  // ring slot of weight tile 2s
+  int rs = 0;     // token stage of step s
   for (int s = 0; s < nk; ++s) {
-    const int st = s & 1;
-    m_done = m_run;  // complete once s is the last step
-    // Weight tile 2s has landed: the younger loads (W(2s+1), X x4, W(2s+2)) may still fly.
-    // Our own LDS writes of the previous step are done.
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * kWL + 4) : "memory");
-    __builtin_amdgcn_s_barrier();  // token stage st and its factors are complete; stage st^1 is free
-
-    const uint32_t xst = st * kQXStageB;
+    const int rs1 = rs == 2 ? 0 : rs + 1;     // stage of step s+1
+    const int ws = rs1 == 2 ? 0 : rs1 + 1;    // stage written in this step
     const int slot1 = wslot == 2 ? 0 : wslot + 1;
-    // rescale factors of this step's tile for this lane's four tokens
-    float corr[4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-      const uint32_t ca = lds_base + kQCorrBase + (st * kQM + 32 * mi + i32) * 4;
-      asm volatile("ds_read_b32 %0, %1" : "=v"(corr[mi]) : "v"(ca));
-    }
+    const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
 
-    // Fragment registers: one 32-byte operand = two 128-bit halves.  The fragments of the
-    // second weight tile are fetched into the registers of the first as those fall dead
-    // (an operand is dead once the last MFMA that reads it has been issued; LDS data
-    // comes back long after that MFMA has read its sources).
-    u32x4 a0_lo, a0_hi, a1_lo, a1_hi, b0_lo, b0_hi, b1_lo, b1_hi, b2_lo, b2_hi, b3_lo, b3_hi;
-#define RF_READ32(DST, ADDR0, ADDR1, OFF)                                                     \
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST##_lo) : "v"(ADDR0), "n"(OFF));      \
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST##_hi) : "v"(ADDR1), "n"(OFF));
-    // per-step base addresses; token tile mi and channel tile ni are immediate offsets
-    const uint32_t xa00 = xaddr[0][0] + xst, xa01 = xaddr[0][1] + xst;
-    const uint32_t xa10 = xaddr[1][0] + xst, xa11 = xaddr[1][1] + xst;
-    const uint32_t wa0_0 = waddr[0][0] + wslot * kQWSlotB, wa0_1 = waddr[0][1] + wslot * kQWSlotB;
-    const uint32_t wa1_0 = waddr[0][0] + slot1 * kQWSlotB, wa1_1 = waddr[0][1] + slot1 * kQWSlotB;
-#define RF_READ_A(DST, NI, TILE) RF_READ32(DST, wa##TILE##_0, wa##TILE##_1, (NI) * 32 * 64)
-#define RF_READ_B(DST, MI, KK) RF_READ32(DST, xa##KK##0, xa##KK##1, (MI) * 4096)
-    // wait until at most PENDING LDS operations are in flight; the named operand is tied
-    // to the wait so that its uses stay behind it
-#define RF_WAIT2(X, Y, PENDING)                                                               \
-  asm volatile("s_waitcnt lgkmcnt(%4)"                                                        \
-               : "+v"(X##_lo), "+v"(X##_hi), "+v"(Y##_lo), "+v"(Y##_hi)                       \
-               : "n"(PENDING));
-#define RF_WAIT1(X, PENDING) \
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(X##_lo), "+v"(X##_hi) : "n"(PENDING));
-#define RF_MFMA(NI, MI, A, B)                                                                 \
-  {                                                                                           \
-    i32x8 av_, bv_;                                                                           \
-    av_[0] = A##_lo[0]; av_[1] = A##_lo[1]; av_[2] = A##_lo[2]; av_[3] = A##_lo[3];           \
-    av_[4] = A##_hi[0]; av_[5] = A##_hi[1]; av_[6] = A##_hi[2]; av_[7] = A##_hi[3];           \
-    bv_[0] = B##_lo[0]; bv_[1] = B##_lo[1]; bv_[2] = B##_lo[2]; bv_[3] = B##_lo[3];           \
-    bv_[4] = B##_hi[0]; bv_[5] = B##_hi[1]; bv_[6] = B##_hi[2]; bv_[7] = B##_hi[3];           \
-    acc[NI][MI] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                            \
-        av_, bv_, acc[NI][MI], 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);                           \
-  }
-#define RF_FENCE __builtin_amdgcn_sched_barrier(0);
-
-    // fragments of weight tile 2s: 10 + kA1 x 128 bits, in the order of their first use
-    RF_READ_A(a0, 0, 0)
-    RF_READ_B(b0, 0, 0) RF_READ_B(b1, 1, 0) RF_READ_B(b2, 2, 0) RF_READ_B(b3, 3, 0)
-    if constexpr (NI == 2) { RF_READ_A(a1, 1, 0) }
-    // the factors (issued first) are back once at most the fragment reads are in flight
-    asm volatile("s_waitcnt lgkmcnt(%4)"
-                 : "+v"(corr[0]), "+v"(corr[1]), "+v"(corr[2]), "+v"(corr[3])
-                 : "n"(10 + kA1));
+    if (resc) {  // a maximum moved in this step's token tile: rescale (uniform)
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-      if (__builtin_amdgcn_ballot_w64(corr[mi] != 1.0f) != 0) {  // a maximum moved: rescale (uniform)
+      for (int mi = 0; mi < 4; ++mi) {
+        if (__builtin_amdgcn_ballot_w64(corrv[mi] != 1.0f) != 0) {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+          for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[ni][mi][r] *= corr[mi];
+            for (int r = 0; r < 16; ++r) acc[ni][mi][r] *= corrv[mi];
+        }
       }
     }
     RF_FENCE
 
-    // ---- weight tile 2s ----
+    // ---- weight tile 2s, first channel block; maximum of token tile s+2 ----
     RF_WAIT2(a0, b0, 6 + kA1)
     RF_MFMA(0, 0, a0, b0)
-    RF_WAIT_X2(0, 1, 2 * kWL + 2)  // token pieces 0, 1 of tile s+1: W(2s+1), X2, X3, W(2s+2) may still fly
+    RF_WAIT_X2(xreg, 0, 1, kWL + 2)  // token pieces 0, 1 of tile s+2: X2, X3, W(2s+2) may still fly
     amax_bits = __builtin_bit_cast(unsigned, __builtin_elementwise_max(absmax8(xreg[0]), absmax8(xreg[1])));
     RF_FENCE
     RF_WAIT1(b1, 4 + kA1)
     RF_MFMA(0, 1, a0, b1)
-    RF_WAIT_X2(2, 3, kWL)  // pieces 2, 3: W(2s+2) may still fly
+    RF_WAIT_X2(xreg, 2, 3, kWL)  // pieces 2, 3: W(2s+2) may still fly; W(2s+1) has landed
     amax = fold_max(__builtin_elementwise_max(
         __builtin_bit_cast(u16x2, amax_bits), __builtin_elementwise_max(absmax8(xreg[2]), absmax8(xreg[3]))));
-    update_max(st ^ 1);
     RF_FENCE
     RF_WAIT1(b2, 2 + kA1)
     RF_MFMA(0, 2, a0, b2)
+    update_max(ws);
     RF_FENCE
-    RF_WAIT1(b3, kA1)
+    RF_WAIT1(b3, 1 + kA1)  // (+1: the factor write of update_max)
     RF_MFMA(0, 3, a0, b3)
     RF_FENCE
-    if constexpr (NI == 2) { RF_WAIT1(a1, 0) }  // every read of ring slot wslot is back
-    RF_QUANT_STORE(0, st ^ 1)
-    RF_LOAD_X(0, min(s + 2, nk - 1))
-    RF_QUANT_STORE(1, st ^ 1)
-    RF_LOAD_X(1, min(s + 2, nk - 1))
-    RF_READ_A(a0, 0, 1)       // first operand of weight tile 2s+1
-    if constexpr (NI == 2) { RF_MFMA(1, 0, a1, b0) }
-    RF_READ_B(b0, 0, 1)
-    RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)  // refill the slot just read
-    RF_FENCE
-    if constexpr (NI == 2) { RF_MFMA(1, 1, a1, b1) }
-    RF_READ_B(b1, 1, 1)
-    RF_FENCE
-    if constexpr (NI == 2) { RF_MFMA(1, 2, a1, b2) }
-    RF_READ_B(b2, 2, 1)
-    RF_FENCE
-    if constexpr (NI == 2) { RF_MFMA(1, 3, a1, b3) }
-    RF_READ_B(b3, 3, 1)
-    if constexpr (NI == 2) { RF_READ_A(a1, 1, 1) }
+    // Every wavefront has finished step s-1 when it gets here: stage rs1 and its factors are
+    // complete, stage ws is free.  (Our own LDS writes of step s-1 are older than the fragments
+    // waited for above.)
+    __builtin_amdgcn_s_barrier();
     RF_FENCE
 
-    // ---- weight tile 2s+1 ----
-    // LDS operations in flight, oldest first: two piece writes, a0, b0, b1, b2, b3, (a1)
-    RF_WAIT2(a0, b0, 6 + kA1)
-    RF_MFMA(0, 0, a0, b0)
-    RF_FENCE
-    RF_WAIT1(b1, 4 + kA1)
-    RF_MFMA(0, 1, a0, b1)
-    RF_FENCE
-    RF_WAIT1(b2, 2 + kA1)
-    RF_MFMA(0, 2, a0, b2)
-    RF_FENCE
-    RF_WAIT1(b3, kA1)
-    RF_MFMA(0, 3, a0, b3)
-    RF_FENCE
-    if constexpr (NI == 2) { RF_WAIT1(a1, 0) }  // every read of ring slot slot1 is back
-    RF_QUANT_STORE(2, st ^ 1)
-    RF_LOAD_X(2, min(s + 2, nk - 1))
-    RF_QUANT_STORE(3, st ^ 1)
-    RF_LOAD_X(3, min(s + 2, nk - 1))
+    // ---- second channel block of tile 2s; fragments of tile 2s+1; token pieces 0, 1 ----
+    // The quantisation is cut into half pieces (4 values), one behind each MFMA from here on.
+    int qa;  // first four codes of the piece in work
+    const uint32_t xw = xdst_addr0 + ws * kQXStageB;
+    // tile 2s+1: k half 1 of stage rs, ring slot slot1
+    const uint32_t xb0 = xaddr[1][0] + rs * kQXStageB, xb1 = xaddr[1][1] + rs * kQXStageB;
+    const uint32_t wb0 = waddr[0] + slot1 * kQWSlotB, wb1 = waddr[1] + slot1 * kQWSlotB;
+    const uint32_t cr1 = corr_raddr + rs1 * (kQM * 4);
+    if constexpr (NI == 2) { RF_WAIT1(a1, 1) }  // every read of ring slot wslot is back (the factor write may fly)
+    asm volatile("ds_read_b128 %0, %1" : "=v"(corrv) : "v"(cr1));  // factors of step s+1
+    RF_READ32(a0, wb0, wb1, 0)   // first operand of weight tile 2s+1
     if constexpr (NI == 2) { RF_MFMA(1, 0, a1, b0) }
+    RF_READ32(b0, xb0, xb1, 0 * 4096)
+    RF_QUANT_A(xreg, 0, qa)
+    RF_FENCE
+    if constexpr (NI == 2) { RF_MFMA(1, 1, a1, b1) }
+    RF_READ32(b1, xb0, xb1, 1 * 4096)
+    RF_QUANT_B(xreg, 0, qa, xw)
+    RF_LOAD_X(xreg, 0, min(s + 3, nk - 1))
+    RF_ISSUE_W(min(2 * s + 3, nkk - 1), wslot)  // refill the slot just read
+    RF_FENCE
+    if constexpr (NI == 2) { RF_MFMA(1, 2, a1, b2) }
+    RF_READ32(b2, xb0, xb1, 2 * 4096)
+    RF_QUANT_A(xreg, 1, qa)
+    RF_FENCE
+    if constexpr (NI == 2) { RF_MFMA(1, 3, a1, b3) }
+    RF_READ32(b3, xb0, xb1, 3 * 4096)
+    if constexpr (NI == 2) { RF_READ32(a1, wb0, wb1, 32 * 64) }
+    RF_QUANT_B(xreg, 1, qa, xw)
+    RF_LOAD_X(xreg, 1, min(s + 3, nk - 1))
+    RF_FENCE
+
+    // ---- weight tile 2s+1, first channel block; token pieces 2, 3 ----
+    // LDS operations in flight, oldest first: the factors, a0, b0, b1, piece write, b2, b3, (a1), piece write
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a0), "+v"(b0), "+v"(corrv) : "n"(8 + kA1));
+    RF_MFMA(0, 0, a0, b0)
+    resc = any_rescale();
+    RF_QUANT_A(xreg, 2, qa)
+    RF_FENCE
+    RF_WAIT1(b1, 6 + kA1)
+    RF_MFMA(0, 1, a0, b1)
+    RF_QUANT_B(xreg, 2, qa, xw)
+    RF_LOAD_X(xreg, 2, min(s + 3, nk - 1))
+    RF_FENCE
+    RF_WAIT1(b2, 4 + kA1)  // b3, (a1) and two piece writes may fly
+    RF_MFMA(0, 2, a0, b2)
+    RF_QUANT_A(xreg, 3, qa)
+    RF_FENCE
+    RF_WAIT1(b3, 2 + kA1)
+    RF_MFMA(0, 3, a0, b3)
+    RF_QUANT_B(xreg, 3, qa, xw)
+    RF_LOAD_X(xreg, 3, min(s + 3, nk - 1))
+    RF_FENCE
+
+    // ---- second channel block of tile 2s+1; fragments of tile 2s+2 for the next step ----
+    if constexpr (NI == 2) { RF_WAIT1(a1, 3) }  // every read of ring slot slot1 is back (three piece writes may fly)
+    // tile 2s+2: k half 0 of stage rs1, ring slot slot2
+    const uint32_t xn0 = xaddr[0][0] + rs1 * kQXStageB, xn1 = xaddr[0][1] + rs1 * kQXStageB;
+    const uint32_t wn0 = waddr[0] + slot2 * kQWSlotB, wn1 = waddr[1] + slot2 * kQWSlotB;
+    // weight tile 2s+2 has landed: the younger requests (X0, W(2s+3), X1, X2, X3) may still fly
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWL + 4) : "memory");
+    RF_READ32(a0, wn0, wn1, 0)   // first operand of weight tile 2s+2
+    if constexpr (NI == 2) { RF_MFMA(1, 0, a1, b0) }
+    RF_READ32(b0, xn0, xn1, 0 * 4096)
     RF_ISSUE_W(min(2 * s + 4, nkk - 1), slot1)
     RF_FENCE
-    if constexpr (NI == 2) {
-      RF_MFMA(1, 1, a1, b1)
-      RF_MFMA(1, 2, a1, b2)
-      RF_MFMA(1, 3, a1, b3)
-    }
+    if constexpr (NI == 2) { RF_MFMA(1, 1, a1, b1) }
+    RF_READ32(b1, xn0, xn1, 1 * 4096)
     RF_FENCE
+    if constexpr (NI == 2) { RF_MFMA(1, 2, a1, b2) }
+    RF_READ32(b2, xn0, xn1, 2 * 4096)
+    RF_FENCE
+    if constexpr (NI == 2) { RF_MFMA(1, 3, a1, b3) }
+    RF_READ32(b3, xn0, xn1, 3 * 4096)
+    if constexpr (NI == 2) { RF_READ32(a1, wn0, wn1, 32 * 64) }
+    RF_FENCE
+    wslot = slot2;
+    rs = rs1;
+  }
+  // the surplus requests stay reserved until they have landed
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"
+               : "+v"(xreg[0]), "+v"(xreg[1]), "+v"(xreg[2]), "+v"(xreg[3]), "+v"(a0), "+v"(b0), "+v"(b1),
+                 "+v"(b2), "+v"(b3)
+               :
+               : "memory");
+  if constexpr (NI == 2) asm volatile("" : "+v"(a1));
 #undef RF_READ32
-#undef RF_READ_A
-#undef RF_READ_B
 #undef RF_WAIT2
 #undef RF_WAIT1
 #undef RF_MFMA
 #undef RF_FENCE
-    wslot = wslot == 0 ? 2 : wslot - 1;  // (wslot + 2) % 3
-  }
-  // (the registers of the surplus prefetch stay reserved until it has landed)
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"
-               : "+v"(xreg[0]), "+v"(xreg[1]), "+v"(xreg[2]), "+v"(xreg[3])
-               :
-               : "memory");
 #undef RF_ISSUE_W
 #undef RF_LOAD_X
 #undef RF_WAIT_X2
 #undef RF_QUANT_STORE
+#undef RF_QUANT_A
+#undef RF_QUANT_B
 
   // final maxima of the tokens, to the accumulator lanes through LDS
-  if (xq == 0) s_mfinal[xrow] = m_done;
+  if (xq == 0) s_mfinal[xrow] = m_run;
   __syncthreads();
 
   // epilogue: c = acc * m / MAX

@@ -21,6 +21,12 @@ with the most operations in flight goes on.  Each backward branch is then taken 
 its target with the queue it had at the branch, which covers the steady state of a
 software-pipelined loop.
 
+The same walk checks one hazard of inline-assembly dot instructions (``v_dot2c_f32_bf16`` and
+its kin): their result may be read by an instruction of another kind only after three wait
+states, which the compiler inserts behind dot instructions that it emits itself but not behind
+one written in an ``asm`` statement.  An instruction counts as one wait state, ``s_nop N`` as
+N + 1.
+
 ``python -m paper_2603_10026_amd.check_isa file.hip [...]`` prints what it finds and exits
 non-zero on a hazard.
 """
@@ -84,18 +90,20 @@ class Queues:
     """In-flight operations of the two counters that the kernels wait on by hand: vector
     memory (vmcnt) and LDS / scalar memory (lgkmcnt).  Entries are (registers, text, kind)."""
 
-    def __init__(self, vm=None, lgkm=None):
+    def __init__(self, vm=None, lgkm=None, dots=None):
         self.vm = list(vm or [])
         self.lgkm = list(lgkm or [])
+        self.dots = list(dots or [])   # [registers, text, wait states since] of recent dot instructions
 
     def copy(self):
-        return Queues(self.vm, self.lgkm)
+        return Queues(self.vm, self.lgkm, [list(d) for d in self.dots])
 
 
 def _step(ins, q, where, report, counters=("vm", "lgkm")):
     """Apply one instruction to the queues of in-flight operations; hazards are reported for
     the named counters only."""
     mnem, _, ops = ins.partition(" ")
+    _dot_hazard(mnem, ops, ins, q, where, report)
     if mnem == "s_waitcnt":
         m = _VMCNT.search(ops)
         if m:
@@ -135,6 +143,28 @@ def _step(ins, q, where, report, counters=("vm", "lgkm")):
         elif "atomic" in mnem and re.search(r"\b(sc0|glc)\b", ops):
             dest = _regs(ops.split(",")[0])
         q.vm.append((dest, ins, "vmem"))
+
+
+_DOT_WAIT_STATES = 3
+
+
+def _dot_hazard(mnem, ops, ins, q, where, report):
+    """Wait states between a dot instruction and a reader of another kind."""
+    if q.dots and mnem.startswith("v_") and not mnem.startswith("v_dot"):
+        named = _regs(ops)
+        for dest, issued, age in q.dots:
+            if age < _DOT_WAIT_STATES and named & dest:
+                report.append(f"{where}: `{ins}` reads v{min(named & dest)} {age} wait states after `{issued}`")
+                break
+    passed = 1
+    if mnem == "s_nop":
+        try:
+            passed = int(ops.strip(), 0) + 1
+        except ValueError:
+            passed = 1
+    q.dots = [[d, t, a + passed] for d, t, a in q.dots if a + passed < _DOT_WAIT_STATES]
+    if mnem.startswith("v_dot"):
+        q.dots.append([_regs(ops.split(",")[0]), ins, 0])
 
 
 def _longest(states):

@@ -82,6 +82,21 @@ def test_lds_reads_waited_by_count_and_scalar_loads_in_between():
     assert only_lgkm == []
 
 
+def test_dot_result_needs_three_wait_states_before_another_kind_of_reader():
+    dot = "\tv_dot2c_f32_bf16 v180, v20, v20\n"
+    # a copy one instruction later reads the old value
+    hz = hazards(dot + "\ts_addc_u32 s11, s11, s9\n\tv_mov_b32_e32 v193, v180\n")
+    assert len(hz) == 1 and "v180" in hz[0] and "wait states" in hz[0]
+    # three other instructions, or a nop that stands for them, are enough
+    assert hazards(dot + "\ts_add_u32 s0, s0, s1\n" * 3 + "\tv_mov_b32_e32 v193, v180\n") == []
+    assert hazards(dot + "\ts_nop 2\n\tv_mov_b32_e32 v193, v180\n") == []
+    assert len(hazards(dot + "\ts_nop 1\n\tv_mov_b32_e32 v193, v180\n")) == 1
+    # the next dot instruction may accumulate into the same register right away
+    assert hazards(dot + "\tv_dot2c_f32_bf16 v180, v21, v21\n\ts_nop 3\n\tv_mov_b32_e32 v1, v180\n") == []
+    # other registers are free to be read
+    assert hazards(dot + "\tv_mov_b32_e32 v193, v181\n") == []
+
+
 def test_sources_with_hand_counted_loads_are_found_and_clean():
     checked = {s: C.hand_counted(os.path.join(B.CSRC, s)) for s in B.SOURCES}
     checked = {s: c for s, c in checked.items() if c}

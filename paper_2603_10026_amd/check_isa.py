@@ -25,7 +25,10 @@ The same walk checks one hazard of inline-assembly dot instructions (``v_dot2c_f
 its kin): their result may be read by an instruction of another kind only after three wait
 states, which the compiler inserts behind dot instructions that it emits itself but not behind
 one written in an ``asm`` statement.  An instruction counts as one wait state, ``s_nop N`` as
-N + 1.
+N + 1.  Likewise a scalar register written by a vector instruction (``v_readfirstlane_b32``,
+``v_readlane_b32``) may be read by a vector-memory instruction only after five wait states;
+the compiler sees to that for its own memory instructions, not for one inside an ``asm``
+statement whose base address it has just moved to scalar registers.
 
 ``python -m paper_2603_10026_amd.check_isa file.hip [...]`` prints what it finds and exits
 non-zero on a hazard.
@@ -94,9 +97,12 @@ class Queues:
         self.vm = list(vm or [])
         self.lgkm = list(lgkm or [])
         self.dots = list(dots or [])   # [registers, text, wait states since] of recent dot instructions
+        self.lane_reads = []           # [scalar registers, text, wait states since] of recent v_readlane's
 
     def copy(self):
-        return Queues(self.vm, self.lgkm, [list(d) for d in self.dots])
+        q = Queues(self.vm, self.lgkm, [list(d) for d in self.dots])
+        q.lane_reads = [list(d) for d in self.lane_reads]
+        return q
 
 
 def _step(ins, q, where, report, counters=("vm", "lgkm")):
@@ -146,6 +152,19 @@ def _step(ins, q, where, report, counters=("vm", "lgkm")):
 
 
 _DOT_WAIT_STATES = 3
+_LANE_READ_WAIT_STATES = 5
+_SREG = re.compile(r"\bs(\d+)\b|\bs\[(\d+):(\d+)\]")
+
+
+def _sregs(text):
+    out = set()
+    for m in _SREG.finditer(text):
+        if m.group(1) is not None:
+            out.add(int(m.group(1)))
+        else:
+            out.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
 
 
 def _dot_hazard(mnem, ops, ins, q, where, report):
@@ -165,6 +184,16 @@ def _dot_hazard(mnem, ops, ins, q, where, report):
     q.dots = [[d, t, a + passed] for d, t, a in q.dots if a + passed < _DOT_WAIT_STATES]
     if mnem.startswith("v_dot"):
         q.dots.append([_regs(ops.split(",")[0]), ins, 0])
+    # scalar register written by a vector instruction, then read by a vector-memory instruction
+    if q.lane_reads and mnem.startswith(_VM_PREFIX):
+        named = _sregs(ops)
+        for dest, issued, age in q.lane_reads:
+            if age < _LANE_READ_WAIT_STATES and named & dest:
+                report.append(f"{where}: `{ins}` reads s{min(named & dest)} {age} wait states after `{issued}`")
+                break
+    q.lane_reads = [[d, t, a + passed] for d, t, a in q.lane_reads if a + passed < _LANE_READ_WAIT_STATES]
+    if mnem in ("v_readfirstlane_b32", "v_readlane_b32"):
+        q.lane_reads.append([_sregs(ops.split(",")[0]), ins, 0])
 
 
 def _longest(states):

@@ -78,7 +78,10 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
   constexpr int kBQ = 32 * NW;               // query rows per workgroup
   constexpr int LD_PER_WAVE = kBK / ROWS_PER_LD / kWaves;
 
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * TILEB];  // [buf][K,V]
+  // Two K/V slots.  Layout: the K slots, then the V slots; the K address registers point at the
+  // first K slot, the V registers at the first V slot.
+  constexpr int NS = 2;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * NS * TILEB];  // [K,V][slot]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -114,9 +117,14 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
     qt = n_units - 1 - (int)(blockIdx.x / n_bh);
     bh = blockIdx.x % n_bh;
   }
-  const int h = bh % Hq;
-  const int b = bh / Hq;
-  const int hk = h / (Hq / Hkv);
+  // (integer division runs on the vector unit even for wave-uniform operands: hand the results
+  // back to the scalar unit here, once, so that everything derived from them, the K/V base
+  // pointers of the direct-to-LDS loads above all, is scalar)
+  qt = __builtin_amdgcn_readfirstlane(qt);
+  bh = __builtin_amdgcn_readfirstlane(bh);
+  const int h = __builtin_amdgcn_readfirstlane(bh % Hq);
+  const int b = __builtin_amdgcn_readfirstlane(bh / Hq);
+  const int hk = __builtin_amdgcn_readfirstlane(h / (Hq / Hkv));
   const bf16_t* qb = q + (int64_t)b * sq.b + (int64_t)h * sq.h;
   const bf16_t* kb = k + (int64_t)b * sk.b + (int64_t)hk * sk.h;
   const bf16_t* vb = v + (int64_t)b * sv.b + (int64_t)hk * sv.h;
@@ -125,34 +133,35 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
   scale_log2e = scale_zero ? 1.0f : fabsf(scale_log2e);
 
   // ---- direct-to-LDS load geometry: this lane's row / slot in each of its loads ----
-  int ld_row[LD_PER_WAVE];
-  int ld_kcol[LD_PER_WAVE], ld_vcol[LD_PER_WAVE];  // element offsets inside the global row
+  // load e of a wavefront covers rows (wave * LD_PER_WAVE + e) * ROWS_PER_LD + lane / P, one
+  // 16-byte slot per lane; the slot holds the piece that the swizzle puts there
+  auto ld_row = [&](int e, int ln) { return (wave * LD_PER_WAVE + e) * ROWS_PER_LD + ln / P; };
+  auto ld_col = [&](int e, int ln, int is_v) {  // element offset inside the global row
+    const int row = ld_row(e, ln), slot = ln % P;
+    return 8 * (slot ^ (is_v ? fV<D>(row) : fK<D>(row)));
+  };
   uint32_t ld_koff[LD_PER_WAVE], ld_voff[LD_PER_WAVE];  // byte offsets from the tile's first row
 #pragma unroll
   for (int e = 0; e < LD_PER_WAVE; ++e) {
-    const int inst = wave * LD_PER_WAVE + e;
-    const int row = inst * ROWS_PER_LD + lane / P;
-    const int slot = lane % P;
-    ld_row[e] = row;
-    ld_kcol[e] = 8 * (slot ^ fK<D>(row));
-    ld_vcol[e] = 8 * (slot ^ fV<D>(row));
-    ld_koff[e] = (uint32_t)(((int64_t)row * sk.l + ld_kcol[e]) * 2);
-    ld_voff[e] = (uint32_t)(((int64_t)row * sv.l + ld_vcol[e]) * 2);
+    ld_koff[e] = (uint32_t)(((int64_t)ld_row(e, lane) * sk.l + ld_col(e, lane, 0)) * 2);
+    ld_voff[e] = (uint32_t)(((int64_t)ld_row(e, lane) * sv.l + ld_col(e, lane, 1)) * 2);
   }
   // byte offsets stay below 2^32 inside one 64-row tile only if the row stride does
   const bool small_stride = sk.l < (1 << 24) && sv.l < (1 << 24);
   // One direct-to-LDS load of this wavefront's share of the tile at key0: load e of K
   // (is_v = 0) or of V (is_v = 1) into buffer buf.
+  const uint32_t lds_base =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  // LDS address of this wavefront's first load in K slot 0, on the scalar unit
+  const uint32_t dma_base = __builtin_amdgcn_readfirstlane(lds_base + wave * LD_PER_WAVE * 1024);
   auto issue_one = [&](int key0, int buf, int e, int is_v) {
-    unsigned char* dst = lds + buf * 2 * TILEB + is_v * TILEB + (wave * LD_PER_WAVE + e) * 1024;
+    const uint32_t dst_addr = dma_base + is_v * NS * TILEB + buf * TILEB + e * 1024;
     const bf16_t* base = is_v ? vb : kb;
     const int64_t ld = is_v ? sv.l : sk.l;
     if (key0 + kBK <= Lk && small_stride) {
       // full tile: uniform tile base + per-lane 32-bit offset, no per-load address math
       // (raw instruction: scalar base + 32-bit lane offset, LDS destination in M0)
       const char* tile = reinterpret_cast<const char*>(base) + (int64_t)key0 * ld * 2;
-      const uint32_t dst_addr = __builtin_amdgcn_readfirstlane(
-          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)dst);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(dst_addr), "v"(is_v ? ld_voff[e] : ld_koff[e]), "s"(tile)
@@ -162,10 +171,12 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
       // instruction with a 64-bit lane address: every direct-to-LDS load of this kernel goes
       // through one mechanism, so M0 is only ever written here, in statements that declare it
       // as clobbered.
-      const int key = min(key0 + ld_row[e], Lk - 1);
-      const bf16_t* src = base + (int64_t)key * ld + (is_v ? ld_vcol[e] : ld_kcol[e]);
-      const uint32_t dst_addr = __builtin_amdgcn_readfirstlane(
-          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)dst);
+      // (an opaque copy of the lane number: the address pieces of this rare path are then
+      // computed here, not ahead of the loop, where they would occupy registers all along)
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int key = min(key0 + ld_row(e, ln), Lk - 1);
+      const bf16_t* src = base + (int64_t)key * ld + ld_col(e, ln, is_v);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                    :
                    : "s"(dst_addr), "v"(src)
@@ -189,30 +200,31 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
   }
 
   // ---- LDS read offsets (loop invariant) ----
-  int koff[KS];  // + rt * 32 * ROWB
-#pragma unroll
-  for (int kk = 0; kk < KS; ++kk) koff[kk] = i32 * ROWB + (((2 * kk + hh) ^ fK<D>(i32)) << 4);
+  // K fragment of contraction step kk: row i32 (+ 32 rt), slot (2 kk + hh) ^ fK.  The slot index
+  // is an XOR and the row pitch is a multiple of 256, so step kk's address is step 0's with
+  // kk << 5 XOR-ed in: one register instead of one per step.
+  uint32_t koff0 = i32 * ROWB + ((hh ^ fK<D>(i32)) << 4);  // LDS byte address in slot 0; + rt * 32 * ROWB
+  static_assert(ROWB % 256 == 0 || (KS - 1) << 5 < ROWB, "kk << 5 stays inside the row");
   // transpose reads of V: lane = 32hh + 16g2 + 4j + a reads 8 bytes of key row
   // (16u + 8w + 4hh + j) at head-dim offset 32t + 16g2 + 4a; the 16-lane group gets,
   // in lane 4a + e, keys j = 0..3 of head-dim 32t + 16g2 + 4a + e.
-  int voff[DT][2];  // + u * 16 * ROWB
+  // (head-dim tile t enters the slot index as 4 t under an XOR: its address is tile 0's with
+  // t << 6 XOR-ed in)
+  uint32_t voff0[2];  // [w2], tile t = 0; + u * 16 * ROWB
   {
     const int i16 = lane & 15, g2 = (lane >> 4) & 1;
     const int j = i16 >> 2, a = i16 & 3;
 #pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-      for (int w2 = 0; w2 < 2; ++w2) {
-        const int row = 8 * w2 + 4 * hh + j;
-        const int piece = 4 * t + 2 * g2 + (a >> 1);
-        voff[t][w2] = row * ROWB + (((piece ^ fV<D>(row)) & (P - 1)) << 4) + 8 * (a & 1);
-      }
+    for (int w2 = 0; w2 < 2; ++w2) {
+      const int row = 8 * w2 + 4 * hh + j;
+      const int piece = 2 * g2 + (a >> 1);
+      voff0[w2] = row * ROWB + (((piece ^ fV<D>(row)) & (P - 1)) << 4) + 8 * (a & 1);
+    }
   }
 
-  const uint32_t lds_base =
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
-#pragma unroll
-  for (int t = 0; t < DT; ++t) { voff[t][0] += lds_base; voff[t][1] += lds_base; }
+  voff0[0] += lds_base + NS * TILEB;
+  voff0[1] += lds_base + NS * TILEB;
+  koff0 += lds_base;
 
   // Under a causal mask a workgroup may own two query tiles of its head, the one that sees the
   // most keys paired with the one that sees the fewest and so on inwards: every workgroup of the
@@ -257,64 +269,91 @@ __global__ __launch_bounds__(NW * kWave, NW == 4 ? 2 : 1) void attention_bf16_ke
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-  // One key tile.  BUF is a compile-time constant so that every LDS access of the
-  // tile is a loop-invariant register plus an immediate offset.
+  // K fragments of one tile: all of them are requested at once (LDS latency is paid once per
+  // tile, not once per contraction step), as raw instructions waited for by hand: through the
+  // compiler they would wait for the direct-to-LDS loads in flight.
+  // (the addresses are formed from an opaque copy of the base, here and for V below: otherwise
+  // the compiler forms all of them ahead of the loop and carries them in registers)
+#define RF_ISSUE_K(KF, SLOT)                                                              \
+  {                                                                                       \
+    uint32_t kb_ = koff0;                                                                 \
+    asm volatile("" : "+v"(kb_));                                                         \
+    _Pragma("unroll") for (int kk = 0; kk < KS; ++kk) {                                   \
+      const uint32_t ka_ = kb_ ^ (kk << 5);                                               \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(KF[kk][0]) : "v"(ka_), "n"((SLOT) * TILEB)); \
+      asm volatile("ds_read_b128 %0, %1 offset:%2"                                        \
+                   : "=v"(KF[kk][1]) : "v"(ka_), "n"((SLOT) * TILEB + 32 * ROWB));        \
+    }                                                                                     \
+  }
+
+  // One key tile.  BUF is a compile-time constant so that every LDS access of the tile is a
+  // register plus an immediate offset.
   auto tile_step = [&](int kt, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
+    constexpr int FILL = BUF ^ 1;   // slot of the tile requested during this one
     const int key0 = kt * kBK;
     wait_vmem_all();   // this wavefront's share of tile kt has landed
-    __syncthreads();   // everyone's share has landed; everyone is done reading the other buffer
+    __syncthreads();   // everyone's share has landed; everyone is done reading the other slot
     const bool more = kt + 1 < n_ktiles;
     if (key0 > wave_last) {  // nothing visible for this wavefront (uniform): only fetch its share
-      if (more) issue_loads(key0 + kBK, BUF ^ 1);
+      if (more) issue_loads(key0 + kBK, FILL);
       return;
     }
-
-    const unsigned char* kt_lds = lds + BUF * 2 * TILEB;
+    u32x4 kq[KS][2];
+    RF_ISSUE_K(kq, BUF)
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
-    // All K fragments are requested before the first MFMA: LDS latency is paid once per
-    // tile, not once per contraction step.
     f32x16 s[2];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[rt][r] = 0.f;
-    u32x4 kf[KS][2];
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-        kf[kk][rt] = *reinterpret_cast<const u32x4*>(kt_lds + koff[kk] + rt * 32 * ROWB);
     __builtin_amdgcn_sched_barrier(0);
     // The loads of the next tile are issued one at a time between the MFMAs.  Issued in a
     // burst right after the barrier, the eight wavefronts of a CU queue up behind each
     // other in the vector-memory unit and every one of them idles for the whole burst.
     constexpr int kIssueEvery = KS / (2 * LD_PER_WAVE);  // contraction steps per load
     static_assert(kIssueEvery * 2 * LD_PER_WAVE == KS, "loads spread evenly over the contraction steps");
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-        s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk][rt]),
-                                                        __builtin_bit_cast(bf16x8, qf[kk]), s[rt],
-                                                        0, 0, 0);
+    static_assert(2 * (KS - 1) <= 15, "the wait counts below fit the LDS counter");
+    auto st_step = [&](auto kk_tag) {
+      constexpr int kk = decltype(kk_tag)::value;
+      // the two fragments of this step are back once at most the younger ones are in flight
+      u32x4& k0 = kq[kk][0];
+      u32x4& k1 = kq[kk][1];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(k0), "+v"(k1) : "n"(2 * (KS - 1 - kk)));
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, k0),
+                                                     __builtin_bit_cast(bf16x8, qf[kk]), s[0], 0, 0, 0);
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, k1),
+                                                     __builtin_bit_cast(bf16x8, qf[kk]), s[1], 0, 0, 0);
       if (more && kk % kIssueEvery == 0)
-        issue_one(key0 + kBK, BUF ^ 1, (kk / kIssueEvery) >> 1, (kk / kIssueEvery) & 1);
+        issue_one(key0 + kBK, FILL, (kk / kIssueEvery) >> 1, (kk / kIssueEvery) & 1);
       __builtin_amdgcn_sched_barrier(0);
+    };
+    st_step(std::integral_constant<int, 0>{});
+    st_step(std::integral_constant<int, 1>{});
+    st_step(std::integral_constant<int, 2>{});
+    st_step(std::integral_constant<int, 3>{});
+    if constexpr (KS > 4) {
+      st_step(std::integral_constant<int, 4>{});
+      st_step(std::integral_constant<int, 5>{});
+      st_step(std::integral_constant<int, 6>{});
+      st_step(std::integral_constant<int, 7>{});
     }
+    static_assert(KS == 4 || KS == 8, "contraction steps written out above");
     // ---- V^T fragments of the first two contraction steps: requested now, they arrive
     //      while the softmax below runs on the vector ALU ----
     // The transpose reads are issued as raw instructions and waited for by hand:
     // going through the compiler's intrinsic would make it wait for the
     // direct-to-LDS loads of the NEXT tile before every read of this one.
     u32x2 va[2][DT][2];
+    uint32_t vb_[2] = {voff0[0], voff0[1]};
+    asm volatile("" : "+v"(vb_[0]), "+v"(vb_[1]));
 #define RF_ISSUE_V(STAGE, U)                                                              \
   _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                        \
     _Pragma("unroll") for (int w2 = 0; w2 < 2; ++w2) asm volatile(                        \
         "ds_read_b64_tr_b16 %0, %1 offset:%2"                                             \
         : "=v"(va[STAGE][t][w2])                                                          \
-        : "v"(voff[t][w2]), "n"(BUF * 2 * TILEB + TILEB + (U) * 16 * ROWB));              \
+        : "v"(vb_[w2] ^ (t << 6)), "n"(BUF * TILEB + (U) * 16 * ROWB));                   \
   }
     // wait until at most PENDING transpose reads are still in flight; the registers of
     // STAGE are tied to the wait so that their uses stay behind it

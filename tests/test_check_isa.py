@@ -97,6 +97,17 @@ def test_dot_result_needs_three_wait_states_before_another_kind_of_reader():
     assert hazards(dot + "\tv_mov_b32_e32 v193, v181\n") == []
 
 
+def test_scalar_register_from_a_lane_read_needs_five_wait_states_before_vector_memory():
+    rd = "\tv_readfirstlane_b32 s7, v193\n\tv_readfirstlane_b32 s6, v192\n"
+    ld = "\tglobal_load_lds_dwordx4 v200, s[6:7]\n\ts_waitcnt vmcnt(0)\n"
+    hz = hazards(rd + "\ts_mov_b32 m0, s34\n\ts_nop 0\n" + ld)
+    assert len(hz) == 1 and "s7" in hz[0] and "wait states" in hz[0]
+    assert hazards(rd + "\ts_mov_b32 m0, s34\n\ts_nop 4\n" + ld) == []
+    assert hazards(rd + "\ts_add_u32 s0, s0, s1\n" * 5 + ld) == []
+    # a scalar consumer is interlocked
+    assert hazards(rd + "\ts_mov_b32 m0, s6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v200, s[10:11]\n\ts_waitcnt vmcnt(0)\n") == []
+
+
 def test_sources_with_hand_counted_loads_are_found_and_clean():
     checked = {s: C.hand_counted(os.path.join(B.CSRC, s)) for s in B.SOURCES}
     checked = {s: c for s, c in checked.items() if c}

@@ -25,7 +25,9 @@ The same walk checks one hazard of inline-assembly dot instructions (``v_dot2c_f
 its kin): their result may be read by an instruction of another kind only after three wait
 states, which the compiler inserts behind dot instructions that it emits itself but not behind
 one written in an ``asm`` statement.  An instruction counts as one wait state, ``s_nop N`` as
-N + 1.  Likewise a scalar register written by a vector instruction (``v_readfirstlane_b32``,
+N + 1.  In a source that counts its own waits, a register spill inside a loop is reported as
+well: the compiler waits for the reload with ``vmcnt(0)``, which drains every load the kernel
+keeps in flight.  Likewise a scalar register written by a vector instruction (``v_readfirstlane_b32``,
 ``v_readlane_b32``) may be read by a vector-memory instruction only after five wait states;
 the compiler sees to that for its own memory instructions, not for one inside an ``asm``
 statement whose base address it has just moved to scalar registers.
@@ -233,6 +235,48 @@ def _walk(name, entries, labels, start, end, state, counters, report, tag, back_
         _step(p, state, f"{name} +{i}{tag}", report, counters)
 
 
+def _successors(entries, labels, i):
+    kind, p = entries[i]
+    out = []
+    if kind == "ins":
+        if p.startswith("s_endpgm"):
+            return out
+        m = _BRANCH.match(p)
+        if m and m.group(1) in labels:
+            out.append(labels[m.group(1)])
+            if p.startswith("s_branch"):
+                return out
+    if i + 1 < len(entries):
+        out.append(i + 1)
+    return out
+
+
+def _reachable(entries, labels, start):
+    """Entries that control can reach from `start`."""
+    seen, todo = {start}, [start]
+    while todo:
+        for j in _successors(entries, labels, todo.pop()):
+            if j not in seen:
+                seen.add(j)
+                todo.append(j)
+    return seen
+
+
+def _reaching(entries, labels, goal):
+    """Entries from which control can reach `goal`."""
+    preds = {}
+    for i in range(len(entries)):
+        for j in _successors(entries, labels, i):
+            preds.setdefault(j, []).append(i)
+    seen, todo = {goal}, [goal]
+    while todo:
+        for j in preds.get(todo.pop(), []):
+            if j not in seen:
+                seen.add(j)
+                todo.append(j)
+    return seen
+
+
 def check_kernel(name, entries, counters=("vm", "lgkm")):
     """Return the list of hazards found in one kernel."""
     report = []
@@ -242,6 +286,19 @@ def check_kernel(name, entries, counters=("vm", "lgkm")):
     for target, branch, q in back_edges:
         # from the label itself, so that the walk adopts the state handed to it
         _walk(name, entries, labels, target + 1, branch, q, counters, report, " (second trip)")
+    if counters:
+        # A register spilled inside a loop of a kernel that keeps its own loads in flight: the
+        # compiler waits for its reload with vmcnt(0), which it believes is a wait for that one
+        # load, and every request the kernel has in flight is waited for with it.
+        for target, branch, _ in back_edges:
+            # (a backward branch may also be the way back from a block laid out behind the
+            # function's body: only what can reach the branch from its target is a loop)
+            body = _reachable(entries, labels, target) & _reaching(entries, labels, branch)
+            for i in sorted(body):
+                kind, p = entries[i]
+                if kind == "ins" and p.startswith("scratch_"):
+                    report.append(f"{name} +{i}: `{p}` is a register spill inside a loop")
+                    break
     seen, out = set(), []
     for r in report:
         key = r.split(": ", 1)[1]

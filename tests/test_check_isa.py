@@ -108,6 +108,21 @@ def test_scalar_register_from_a_lane_read_needs_five_wait_states_before_vector_m
     assert hazards(rd + "\ts_mov_b32 m0, s6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v200, s[10:11]\n\ts_waitcnt vmcnt(0)\n") == []
 
 
+def test_spill_inside_a_loop_is_reported_where_waits_are_counted_by_hand():
+    body = (".LBB0_1:\n"
+            "\tscratch_load_dword v9, off, off offset:4\n"
+            "\ts_waitcnt vmcnt(0)\n"
+            "\tv_add_u32_e32 v1, v1, v9\n"
+            "\ts_cbranch_scc1 .LBB0_1\n")
+    hz = hazards(body)
+    assert len(hz) == 1 and "spill inside a loop" in hz[0]
+    # outside a loop a spill is only slow
+    assert hazards("\tscratch_load_dword v9, off, off offset:4\n\ts_waitcnt vmcnt(0)\n") == []
+    # and a source whose waits are all the compiler's is not held to this
+    n, hz = C.check_text(HEAD + body + TAIL, counters=())
+    assert n == 1 and hz == []
+
+
 def test_sources_with_hand_counted_loads_are_found_and_clean():
     checked = {s: C.hand_counted(os.path.join(B.CSRC, s)) for s in B.SOURCES}
     checked = {s: c for s, c in checked.items() if c}

@@ -27,34 +27,47 @@ __global__ __launch_bounds__(NW * kWave) void attention_f32_kernel(
   __shared__ float s_l[NW][16];
   __shared__ float s_acc[NW][16][D + 4];
 
+  // (every argument is named here so that the compiler fetches the whole argument block with its
+  // first scalar loads and waits for it once: fetched where first used, the block came in three
+  // round trips, each behind the wait for the previous one)
+  // (n_qtiles passes through the statement: the index arithmetic below depends on it and so
+  // cannot be scheduled ahead of it)
+  asm volatile("" : "+s"(n_qtiles) : "s"(q), "s"(k), "s"(v), "s"(o), "s"(sq.b), "s"(sq.h), "s"(sq.l), "s"(sk.b),
+               "s"(sk.h), "s"(sk.l), "s"(sv.b), "s"(sv.h), "s"(sv.l), "s"(so.b), "s"(so.h), "s"(so.l),
+               "s"(Hq), "s"(Hkv), "s"(Lq), "s"(Lk), "s"(scale_log2e), "s"(causal));
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int i16 = lane & 15;  // query column / key row / head-dim row inside a tile
   const int g = lane >> 4;    // lane group 0..3
 
-  const int qt = blockIdx.x % n_qtiles;
-  const int bh = blockIdx.x / n_qtiles;
-  const int h = bh % Hq;
-  const int b = bh / Hq;
-  const int hk = h / (Hq / Hkv);
+  // (integer division runs on the vector unit even for wave-uniform operands: the results are
+  // handed back to the scalar unit, so that the base pointers below are scalar)
+  const int qt = __builtin_amdgcn_readfirstlane(blockIdx.x % n_qtiles);
+  const int bh = __builtin_amdgcn_readfirstlane(blockIdx.x / n_qtiles);
+  const int h = __builtin_amdgcn_readfirstlane(bh % Hq);
+  const int b = __builtin_amdgcn_readfirstlane(bh / Hq);
+  const int hk = __builtin_amdgcn_readfirstlane(h / (Hq / Hkv));
   const int q0 = qt * 16;
 
   const float* qb = q + (int64_t)b * sq.b + (int64_t)h * sq.h;
   const float* kb = k + (int64_t)b * sk.b + (int64_t)hk * sk.h;
   const float* vb = v + (int64_t)b * sv.b + (int64_t)hk * sv.h;
+  // At the sizes this kernel serves, the run time is a chain of memory latencies.  All kernel
+  // arguments are therefore fetched in one go (the K/V base pointers are formed here, ahead of
+  // the first load, instead of behind the wait for Q), and Q is read without branches, so
+  // that its loads are only waited for at the first product, with the first K/V group already
+  // on its way.
+  asm volatile("" : : "s"(kb), "s"(vb));
 
   // Q^T fragments.  Contraction slot (g, e) of step j stands for head-dim index
   // 16j + 4g + e on both operands.
   f32x4 qf[DJ];
   {
-    const int qi = q0 + i16;
+    // (rows past the end repeat the last query: their results are computed and never stored)
+    const int qi = min(q0 + i16, Lq - 1);
 #pragma unroll
-    for (int j = 0; j < DJ; ++j) {
-      if (qi < Lq)
-        qf[j] = *reinterpret_cast<const f32x4*>(qb + (int64_t)qi * sq.l + 16 * j + 4 * g);
-      else
-        qf[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int j = 0; j < DJ; ++j)
+      qf[j] = *reinterpret_cast<const f32x4*>(qb + (int64_t)qi * sq.l + 16 * j + 4 * g);
   }
 
   // last visible key of this lane's query, and of the whole query tile

@@ -301,6 +301,13 @@ def main():
             fn(i)
         torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        # A kernel of ~20 us ends before the host has issued the next launch and its two event
+        # records; on an empty queue the first event of a pair is then stamped before the kernel
+        # has been submitted and the pair times the host.  A lead of untimed launches goes first,
+        # with no synchronisation after it, so that the timed launches are queued behind GPU work
+        # and each pair spans one kernel as the GPU runs it.
+        for i in range(64 + 2 * n):
+            fn(i)
         for i in range(n):
             evs[i][0].record()
             fn(warm + i)

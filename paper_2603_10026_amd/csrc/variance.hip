@@ -13,9 +13,12 @@
 //
 // One workgroup (4 wavefronts, or 16 when rows are few and long) streams one row once.  Every lane turns each
 // 128-bit vector into an exact state (two passes over 4 or 8 registers), merges
-// the four vectors of an iteration pairwise (equal counts: no division), and
-// folds the result into its running state; lanes merge through DPP / shuffles,
+// the eight vectors of a chunk pairwise (equal counts: no division), and folds
+// the result into its running state (what is left of a row after the full chunks
+// goes through chunks of 4, 2 and 1 vectors per lane); lanes merge through DPP / shuffles,
 // wavefronts through LDS.  HBM traffic is one read of x.
+#include <type_traits>
+
 #include "rf_device.h"
 #include "rf_launch.h"
 
@@ -90,7 +93,7 @@ __device__ __forceinline__ VarState var_shfl_xor(const VarState& a, int mask) {
   return b;
 }
 
-constexpr int kVarUnroll = 4;  // 128-bit loads in flight per lane
+constexpr int kVarUnroll = 8;  // 128-bit loads in flight per lane in a full chunk
 
 }  // namespace
 
@@ -114,27 +117,36 @@ __global__ __launch_bounds__(kVarWaves * kWave) void variance_kernel(const T* __
     const u32x4* xv = reinterpret_cast<const u32x4*>(xr);
     const int64_t nvec = n / V;  // full vectors
     int64_t base = 0;
-    // full iterations: every lane owns kVarUnroll full vectors
-    for (; base + (int64_t)kVarUnroll * kVarThreads <= nvec; base += (int64_t)kVarUnroll * kVarThreads) {
-      u32x4 raw[kVarUnroll];
+    // a chunk: every lane owns U full vectors, all U loads in flight together
+    auto chunk = [&](auto utag) {
+      constexpr int U = decltype(utag)::value;
+      u32x4 raw[U];
 #pragma unroll
-      for (int u = 0; u < kVarUnroll; ++u)
-        raw[u] = __builtin_nontemporal_load(xv + base + u * kVarThreads + tid);
-      VarState c[kVarUnroll];
+      for (int u = 0; u < U; ++u) raw[u] = __builtin_nontemporal_load(xv + base + u * kVarThreads + tid);
+      VarState c[U];
 #pragma unroll
-      for (int u = 0; u < kVarUnroll; ++u) {
+      for (int u = 0; u < U; ++u) {
         float f[V];
         Elem<T>::unpack(raw[u], f);
         c[u] = var_of_full_vector<V>(f);
       }
-      const VarState c01 = var_merge_equal(c[0], c[1]);
-      const VarState c23 = var_merge_equal(c[2], c[3]);
-      st = var_merge(st, var_merge_equal(c01, c23));
-    }
-    // remaining full vectors, then the ragged tail (fewer than V elements)
-    for (int64_t i = base + tid; i < nvec; i += kVarThreads) {
+      // pairwise tree over the equal-count states
+#pragma unroll
+      for (int w = 1; w < U; w <<= 1) {
+#pragma unroll
+        for (int u = 0; u < U; u += 2 * w) c[u] = var_merge_equal(c[u], c[u + w]);
+      }
+      st = var_merge(st, c[0]);
+      base += (int64_t)U * kVarThreads;
+    };
+    while (base + (int64_t)kVarUnroll * kVarThreads <= nvec) chunk(std::integral_constant<int, kVarUnroll>{});
+    if (base + 4 * (int64_t)kVarThreads <= nvec) chunk(std::integral_constant<int, 4>{});
+    if (base + 2 * (int64_t)kVarThreads <= nvec) chunk(std::integral_constant<int, 2>{});
+    if (base + (int64_t)kVarThreads <= nvec) chunk(std::integral_constant<int, 1>{});
+    // fewer than one vector per lane left, then the ragged tail (fewer than V elements)
+    if (base + tid < nvec) {
       float f[V];
-      Elem<T>::unpack(__builtin_nontemporal_load(xv + i), f);
+      Elem<T>::unpack(__builtin_nontemporal_load(xv + base + tid), f);
       st = var_merge(st, var_of_full_vector<V>(f));
     }
     const int64_t tail0 = nvec * V;

@@ -394,7 +394,9 @@ __global__ __launch_bounds__(kGThreads, 1) void rmsnorm_gemm_bf16_kernel(
       if (m < M) {
         bf16_t* dst = y + (int64_t)m * ldy + n;
         if (n + 8 <= N) {
-          *reinterpret_cast<u32x4*>(dst) = o4;
+          // (non-temporal: the output is not read again here, and leaving it in L2 costs the
+          // X and W panels their place: measured 1 % on 4096^3)
+          __builtin_nontemporal_store(o4, reinterpret_cast<u32x4*>(dst));
         } else if (n + 4 <= N) {
           u32x2 o2;
           o2[0] = o4[0];

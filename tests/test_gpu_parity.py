@@ -262,6 +262,11 @@ SPLIT_CASES = [
     (1, 32, 1, 1, 700, 3, False),      # 32 rows share one KV head: two row tiles
     (1, 4, 2, 3, 300, 5, True),        # Lq > 1, causal, fully masked chunks for early rows
     (1, 2, 2, 1, 1, 1, False),
+    # launches of thousands of workgroups, with chunks shorter than one step of the four wavefronts
+    # (some wavefronts have no tile in a chunk), chunks past the end of the keys, and two row tiles
+    (16, 32, 8, 1, 2560, 64, False),   # chunk 40
+    (8, 16, 16, 1, 4229, 128, False),  # chunk 34, the last chunks short or empty
+    (8, 24, 8, 7, 2880, 64, True),     # chunk 45, 21 rows per KV head, causal
 ]
 
 

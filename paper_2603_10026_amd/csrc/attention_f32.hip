@@ -42,8 +42,14 @@ __global__ __launch_bounds__(NW * kWave) void attention_f32_kernel(
 
   // (integer division runs on the vector unit even for wave-uniform operands: the results are
   // handed back to the scalar unit, so that the base pointers below are scalar)
-  const int qt = __builtin_amdgcn_readfirstlane(blockIdx.x % n_qtiles);
-  const int bh = __builtin_amdgcn_readfirstlane(blockIdx.x / n_qtiles);
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Numbered so that XCD x
+  // takes a run of consecutive (head, query tile) pairs, the query tiles of one head read its K
+  // and V through one L2 instead of eight (batched fp32 launch, 512 heads of 128 x 512 x 64:
+  // 1.09 GB fetched from the fabric before, against 0.15 GB of inputs).
+  int wg = blockIdx.x;
+  if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  const int qt = __builtin_amdgcn_readfirstlane(wg % n_qtiles);
+  const int bh = __builtin_amdgcn_readfirstlane(wg / n_qtiles);
   const int h = __builtin_amdgcn_readfirstlane(bh % Hq);
   const int b = __builtin_amdgcn_readfirstlane(bh / Hq);
   const int hk = __builtin_amdgcn_readfirstlane(h / (Hq / Hkv));

@@ -499,7 +499,8 @@ __global__ __launch_bounds__(kQThreads, 1) void fp8_quant_gemm_kernel(
       const u32x4 o4 = *reinterpret_cast<const u32x4*>(stage + row * RB + ((slot ^ sw) << 4));
       const int m = m0 + row;
       const int n = n0 + L::kWaveN * wave + 8 * slot;
-      if (m < M && n < N) *reinterpret_cast<u32x4*>(c + (int64_t)m * ldc + n) = o4;  // N is a multiple of 8
+      // (N is a multiple of 8; non-temporal like the other matrix kernels' outputs: +2 % on short launches)
+      if (m < M && n < N) __builtin_nontemporal_store(o4, reinterpret_cast<u32x4*>(c + (int64_t)m * ldc + n));
     }
     return;
   }

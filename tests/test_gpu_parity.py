@@ -358,6 +358,9 @@ def test_rmsnorm_gemm_row_scales_and_pitched_output(rf):
 @pytest.mark.parametrize("dtype,bs,l", [
     ("f32", 3, 8192), ("f32", 2, 32768), ("f32", 5, 1000), ("f32", 4, 4099), ("f32", 7, 3), ("f32", 2, 1),
     ("f32", 1, 70001), ("bf16", 3, 8192), ("bf16", 4, 1003), ("bf16", 2, 9), ("bf16", 130, 2048),
+    # rows that end in one chunk of every size (8, 4, 2, 1 vectors per lane), a partial vector round and
+    # a ragged tail: 4-wavefront kernel, then the 16-wavefront kernel (few long rows), fp32 and bf16
+    ("f32", 3, 11666), ("f32", 300, 15669), ("f32", 2, 62643), ("bf16", 2, 125285), ("bf16", 3, 31339),
 ])
 def test_variance_shapes(rf, dtype, bs, l):
     say(f"variance {dtype} bs={bs} l={l}")

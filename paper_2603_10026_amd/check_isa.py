@@ -339,7 +339,7 @@ def hand_counted(path):
     with open(path) as f:
         text = f.read()
     out = []
-    if re.search(r'asm[^;]*"global_load_dwordx\d %0', text):
+    if re.search(r'asm[^;]*global_load_dwordx\d %0', text):
         out.append("vm")
     if re.search(r'asm[^;]*"ds_read\w* %0', text):
         out.append("lgkm")

@@ -343,7 +343,8 @@ def main():
                                                    algorithmic_flops=fl,
                                                    note="fraction of the published fp32 matrix peak (157.3 TFLOP/s); extension of workload 0, not one of the five configurations")
         rooflines.append(dict(kernel="x0_attention_f32_batched", bound="mfma", achieved=round(ach, 2), peak=PEAK_F32_TFLOPS,
-                              unit="TFLOP/s", frac=round(ach / PEAK_F32_TFLOPS, 4), traffic=None, us=round(d["avg"], 2)))
+                              unit="TFLOP/s", frac=round(ach / PEAK_F32_TFLOPS, 4), traffic=traffic.get("x0_attention_f32_batched"),
+                              us=round(d["avg"], 2)))
         del qb, kb_, vb_, ob
     if "x1" in only:
         c = I.EXTRA_WORKLOADS["variance_v8"]
